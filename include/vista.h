@@ -1,0 +1,189 @@
+/*
+ * libvista -- C ABI of the VISTA hot path on one MI355X (gfx950).
+ *
+ * Two stages (paper Sec. 3.1):
+ *   stage 1  vista_summarize      S learned virtual seed embeddings, shared by all
+ *                                 users, attend over each user's jagged history of
+ *                                 L_b items and yield S summary tokens (Sec. 3.2);
+ *   stage 2  vista_target_attend  every candidate item attends, independently, to
+ *                                 its user's S cached summary tokens (Sec. 3.3).
+ * The attention of both stages is the softmax form RowSoftmax(Q K^T) V of
+ * Sec. 3.2.1 (unnumbered equation), multi-head, with scale 1/sqrt(d/H) unless
+ * the descriptor overrides it.
+ *
+ * Conventions for every call
+ *   - All tensor pointers are DEVICE pointers unless the name ends in _host.
+ *     Tensors are row-major and packed; the innermost dimension is d.
+ *   - The caller owns every buffer.  The library allocates nothing, keeps no
+ *     state between calls, never synchronises; all work is enqueued on the
+ *     given hipStream_t (passed as void*; NULL is the default stream).
+ *   - Inputs are read-only; outputs are fully overwritten.
+ *   - Errors are return codes.  Everything that can be checked on the host is
+ *     checked before the first launch; on a non-zero return nothing was enqueued.
+ *   - 64-bit row addressing throughout: N * d may exceed 2^31.
+ */
+#ifndef VISTA_H
+#define VISTA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  VISTA_OK = 0,
+  VISTA_ERR_NULL = 1,        /* a required pointer is NULL */
+  VISTA_ERR_SHAPE = 2,       /* a size is non-positive, d % H != 0, or a stride is inconsistent */
+  VISTA_ERR_OFFSETS = 3,     /* offsets_host: not starting at 0, decreasing, or not ending at total_items */
+  VISTA_ERR_UNSUPPORTED = 4, /* dtype / head width / S outside the supported set */
+  VISTA_ERR_WORKSPACE = 5,   /* workspace pointer NULL, misaligned or too small */
+  VISTA_ERR_HIP = 6          /* a launch failed; hipGetLastError() has the cause */
+} vista_status;
+
+/* storage dtype of every tensor of a call; accumulation is always fp32 */
+enum { VISTA_F32 = 0, VISTA_BF16 = 1 };
+/* score nonlinearity; only the softmax form of Sec. 3.2.1 is built */
+enum { VISTA_ATTN_SOFTMAX = 0 };
+
+/* ---------------------------------------------------------------- stage 1 */
+
+typedef struct {
+  int32_t B;              /* users                                                    */
+  int32_t S;              /* virtual queries = summary tokens per user, 1..512        */
+  int32_t d;              /* model width                                              */
+  int32_t H;              /* heads; head h owns columns [h*d/H, (h+1)*d/H)            */
+  int32_t dtype;          /* VISTA_F32 or VISTA_BF16                                  */
+  int32_t attn;           /* VISTA_ATTN_SOFTMAX                                       */
+  float   scale;          /* score scale; 0 selects 1/sqrt(d/H)                       */
+  int32_t segment_items;  /* items per split-L segment, multiple of 32; 0 = default   */
+  int64_t total_items;    /* N = offsets[B]                                           */
+  int64_t q_user_stride;  /* 0: queries [S,d] shared by all users (Sec. 3.2);
+                             S*d: per-user queries [B,S,d] (stacked layers)           */
+} vista_summarize_desc;
+
+/*
+ * Split-L schedule (the re-association of App. B: partial sums over blocks of
+ * the history may be formed first and combined afterwards).  The packed history
+ * of N rows is cut into G = ceil(N / segment_items) flat segments of equal size;
+ * a segment is processed by one workgroup and is further cut at user
+ * boundaries into pieces.  Piece (g, b) -- the rows of user b inside segment g
+ * -- writes its running maximum, sum of exponentials and un-normalised output
+ * to partial slot g + b; a merge pass combines a user's slots in ascending g.
+ * The schedule is a pure function of (offsets, segment_items), never of the
+ * device, so results are bitwise reproducible.
+ *
+ * vista_summarize_segment_items: the segment size the call will use
+ * (desc->segment_items, or the default derived from total_items alone);
+ * 0 if the descriptor is invalid.
+ */
+int32_t vista_summarize_segment_items(const vista_summarize_desc* desc);
+
+/* Bytes of device workspace vista_summarize needs for this descriptor (0 if invalid).
+ * The workspace must be 256-byte aligned.  Its first 4 bytes receive an int32
+ * device-side status (0 = offsets passed the on-device check, VISTA_ERR_OFFSETS
+ * otherwise) that the caller may read after synchronising the stream. */
+size_t vista_summarize_workspace_bytes(const vista_summarize_desc* desc);
+
+/*
+ * Stage 1 (Sec. 3.2; attention form of Sec. 3.2.1).  For each user b with rows
+ * X_b = history_emb[offsets[b] .. offsets[b+1]-1]:
+ *     K = X_b W_k,  V = X_b W_v,
+ *     out[b][:, head h] = RowSoftmax(scale * Q_h K_h^T) V_h      for every head h,
+ * Q = virtual_queries (shared) or virtual_queries[b] (q_user_stride = S*d).
+ * The softmax of one query runs over all L_b items of that user; there is no
+ * mask and no positional term.  A user with L_b = 0 gets zeros.
+ *
+ *   history_emb      device [N, d]        dtype
+ *   offsets          device int64 [B+1]   offsets[0] = 0, non-decreasing, offsets[B] = N
+ *   offsets_host     host   int64 [B+1]   optional mirror; when given it is validated
+ *                                         here (VISTA_ERR_OFFSETS) before any launch.
+ *                                         When NULL the check runs on the device and
+ *                                         reports through the workspace status word;
+ *                                         kernels clamp every row index to [0, N), so
+ *                                         bad offsets give wrong numbers, never a fault.
+ *   virtual_queries  device [S, d] or [B, S, d]   dtype
+ *   W_k, W_v         device [d, d]        dtype; K = X @ W_k (input rows, output columns)
+ *   out              device [B, S, d]     dtype (bf16: one round-to-nearest-even at the store)
+ *   workspace        device, >= vista_summarize_workspace_bytes(desc), 256-byte aligned
+ *
+ * Supported: bf16 with d/H = 32, d in {128, 256}, S a multiple of 64 (MFMA path);
+ * any dtype with d/H <= 64, d <= 512, S <= 512 (plain fp32-ALU path).
+ */
+vista_status vista_summarize(const vista_summarize_desc* desc,
+                             const void* history_emb,
+                             const int64_t* offsets,
+                             const int64_t* offsets_host,
+                             const void* virtual_queries,
+                             const void* W_k,
+                             const void* W_v,
+                             void* out,
+                             void* workspace, size_t workspace_bytes,
+                             void* hip_stream);
+
+/* ---------------------------------------------------------------- stage 2 */
+
+typedef struct {
+  int32_t B;      /* users                         */
+  int32_t C;      /* candidates per user           */
+  int32_t S;      /* summary tokens per user       */
+  int32_t d;      /* model width                   */
+  int32_t H;      /* heads                         */
+  int32_t dtype;  /* VISTA_F32 or VISTA_BF16       */
+  float   scale;  /* 0 selects 1/sqrt(d/H)         */
+} vista_attend_desc;
+
+/*
+ * Stage 2 (Sec. 3.3).  For each user b, candidate c and head h:
+ *     p = softmax over the S summary tokens of  scale * q . Y_h[j],   q = candidates[b,c,head h]
+ *     out[b,c,head h] = sum_j p_j Y_h[j],                              Y = summaries[b]
+ * The summaries are keys and values at once.  Each candidate is a query row of
+ * its own: candidates never attend to each other (Sec. 3.2.1, remark after Eq. 2).
+ *
+ *   candidates  device [B, C, d]  dtype
+ *   summaries   device [B, S, d]  dtype
+ *   out         device [B, C, d]  dtype
+ *
+ * Supported: bf16 with d/H = 32, S a multiple of 32 up to 512 (MFMA path);
+ * any dtype with d/H <= 64, S <= 512 (plain path).  No workspace.
+ */
+vista_status vista_target_attend(const vista_attend_desc* desc,
+                                 const void* candidates,
+                                 const void* summaries,
+                                 void* out,
+                                 void* hip_stream);
+
+/* ------------------------------------------------ block between layers */
+
+typedef struct {
+  int64_t rows;   /* B * S                          */
+  int32_t d;      /* model width                    */
+  int32_t d_ff;   /* inner width                    */
+  int32_t dtype;  /* VISTA_F32 or VISTA_BF16        */
+  float   eps;    /* 0 selects 1e-6                 */
+} vista_ffn_desc;
+
+/*
+ * SiLU-gated block that turns the summaries of one summarization layer into the
+ * per-user queries of the next (Sec. 3.2.2 names a Simple Gated Linear Unit and
+ * gives no formula; this is the reading this library fixes):
+ *     yhat = y / sqrt(mean_d(y^2) + eps)
+ *     out  = (SiLU(yhat W_g) * (yhat W_u)) W_o
+ *   y    device [rows, d]     W_g, W_u  device [d, d_ff]    W_o  device [d_ff, d]
+ *   out  device [rows, d]     all of dtype
+ * Supported: d <= 512, d_ff <= 1024, both multiples of 32.  No workspace.
+ */
+vista_status vista_sglu_ffn(const vista_ffn_desc* desc,
+                            const void* y,
+                            const void* W_g, const void* W_u, const void* W_o,
+                            void* out,
+                            void* hip_stream);
+
+/* Static, human-readable name of a status code. */
+const char* vista_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VISTA_H */

@@ -1,0 +1,112 @@
+// Shared device helpers of libvista: storage types, the split-L piece walk and
+// the launch-error check.  gfx950 only.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "vista.h"
+
+namespace vista {
+
+// bf16 travels as its 16 bit pattern; fp32 as float.
+struct bf16_t { uint16_t bits; };
+
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(bf16_t v) { return __uint_as_float(uint32_t(v.bits) << 16); }
+
+// Round-to-nearest-even fp32 -> bf16 (finite values; the paths never produce NaN).
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return uint16_t(u >> 16);
+}
+__device__ __forceinline__ void store_as(float* p, float v) { *p = v; }
+__device__ __forceinline__ void store_as(bf16_t* p, float v) { p->bits = f32_to_bf16_bits(v); }
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr int kHeaderBytes = 256;  // workspace header: int32 device status at byte 0
+
+// ---------------------------------------------------------------------------
+// Split-L piece walk (pure function of offsets and the segment size).
+// Segment g owns flat rows [g*seg, min((g+1)*seg, N)).  find_user returns the
+// last user whose first row is <= row; the walk then visits the non-empty
+// intersections of the segment with consecutive users.  Every row handed to a
+// caller lies inside the segment, hence inside [0, N), whatever offsets hold.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ int find_user(const int64_t* __restrict__ offsets, int B, int64_t row) {
+  int lo = 0, hi = B;  // invariant: offsets[lo] <= row (offsets[0] = 0), answer in [lo, hi)
+  while (hi - lo > 1) {
+    int mid = (lo + hi) >> 1;
+    if (offsets[mid] <= row) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+struct Piece {
+  int user;
+  int64_t begin, end;  // flat rows [begin, end)
+};
+
+// Advances to the next piece of segment [pos, seg_end); returns false when done.
+// `user` and `pos` carry the walk state between calls.
+__device__ __forceinline__ bool next_piece(const int64_t* __restrict__ offsets, int B, int64_t seg_end,
+                                           int& user, int64_t& pos, Piece& out) {
+  while (pos < seg_end && user < B) {
+    int64_t uend = offsets[user + 1];
+    if (uend > pos) {
+      int64_t e = uend < seg_end ? uend : seg_end;
+      out.user = user;
+      out.begin = pos;
+      out.end = e;
+      pos = e;
+      if (uend <= seg_end) ++user;
+      return true;
+    }
+    ++user;
+  }
+  return false;
+}
+
+#define VISTA_LAUNCH_CHECK()                                   \
+  do {                                                         \
+    if (hipGetLastError() != hipSuccess) return VISTA_ERR_HIP; \
+  } while (0)
+
+// Launchers implemented in the kernel files (host side).
+struct SummarizeArgs {
+  vista_summarize_desc desc;
+  int seg;            // resolved segment size
+  int64_t G;          // segments
+  float scale_log2;   // scale * log2(e)
+  const void* X;
+  const int64_t* offsets;
+  const void* Q;
+  const void* Wk;
+  const void* Wv;
+  void* out;
+  char* workspace;
+  hipStream_t stream;
+};
+
+size_t generic_summarize_workspace(const vista_summarize_desc& d, int seg);
+vista_status generic_summarize(const SummarizeArgs& a);
+bool mfma_summarize_supported(const vista_summarize_desc& d);
+size_t mfma_summarize_workspace(const vista_summarize_desc& d, int seg);
+vista_status mfma_summarize(const SummarizeArgs& a);
+
+vista_status generic_target_attend(const vista_attend_desc& d, float scale_log2, const void* cand,
+                                   const void* summ, void* out, hipStream_t s);
+bool mfma_target_attend_supported(const vista_attend_desc& d);
+vista_status mfma_target_attend(const vista_attend_desc& d, float scale_log2, const void* cand,
+                                const void* summ, void* out, hipStream_t s);
+
+vista_status generic_sglu_ffn(const vista_ffn_desc& d, float eps, const void* y, const void* Wg,
+                              const void* Wu, const void* Wo, void* out, hipStream_t s);
+bool mfma_sglu_ffn_supported(const vista_ffn_desc& d);
+vista_status mfma_sglu_ffn(const vista_ffn_desc& d, float eps, const void* y, const void* Wg,
+                           const void* Wu, const void* Wo, void* out, hipStream_t s);
+
+void launch_check_offsets(const int64_t* offsets, int B, int64_t N, int* status, hipStream_t s);
+
+}  // namespace vista

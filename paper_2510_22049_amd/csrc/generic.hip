@@ -1,0 +1,311 @@
+// Plain fp32-ALU kernels of libvista: any dtype, any S <= 512, head width <= 64.
+// They carry the fp32 configuration and every shape the MFMA kernels do not
+// take.  One thread owns one query (stage 1) or one (candidate, head) pair
+// (stage 2) and streams the keys with an online softmax in base 2.
+#include "common.hpp"
+
+namespace vista {
+
+constexpr int kMaxDh = 64;
+
+// ------------------------------------------------------------------ checks
+
+__global__ void check_offsets_kernel(const int64_t* __restrict__ offsets, int B, int64_t N,
+                                     int* __restrict__ status) {
+  // One block; thread 0 publishes the verdict after a block-wide OR.
+  __shared__ int bad;
+  if (threadIdx.x == 0) bad = 0;
+  __syncthreads();
+  int local = 0;
+  for (int b = threadIdx.x; b <= B; b += blockDim.x) {
+    int64_t o = offsets[b];
+    if (b == 0 && o != 0) local = 1;
+    if (b == B && o != N) local = 1;
+    if (b < B && offsets[b + 1] < o) local = 1;
+  }
+  if (local) atomicOr(&bad, 1);
+  __syncthreads();
+  if (threadIdx.x == 0) *status = bad ? int(VISTA_ERR_OFFSETS) : 0;
+}
+
+void launch_check_offsets(const int64_t* offsets, int B, int64_t N, int* status, hipStream_t s) {
+  hipLaunchKernelGGL(check_offsets_kernel, dim3(1), dim3(256), 0, s, offsets, B, N, status);
+}
+
+// -------------------------------------------------- stage 1: K/V projection
+// K = X W_k, V = X W_v in fp32 (Sec. 3.2.1: K and V of shape (L, d)).
+// Block = 256 threads = (256/d') rows x d' columns; each thread one (row, col).
+template <typename T>
+__global__ void project_kernel(const T* __restrict__ X, const T* __restrict__ Wk, const T* __restrict__ Wv,
+                               float* __restrict__ K, float* __restrict__ V, int64_t N, int d) {
+  int64_t idx = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (idx >= N * d) return;
+  int64_t row = idx / d;
+  int col = int(idx - row * d);
+  const T* x = X + row * d;
+  float k = 0.f, v = 0.f;
+  for (int t = 0; t < d; ++t) {
+    float xv = to_f32(x[t]);
+    k = fmaf(xv, to_f32(Wk[int64_t(t) * d + col]), k);
+    v = fmaf(xv, to_f32(Wv[int64_t(t) * d + col]), v);
+  }
+  K[idx] = k;
+  V[idx] = v;
+}
+
+// ------------------------------------------- stage 1: streaming attention
+// Partial slot layout: [slot][h][query][dh + 2] fp32 = un-normalised O, then
+// l (sum of 2^(s-m)) and m (running maximum of s, base-2 units).
+template <typename T>
+__global__ void attend_history_kernel(const float* __restrict__ K, const float* __restrict__ V,
+                                      const T* __restrict__ Q, int64_t q_user_stride,
+                                      const int64_t* __restrict__ offsets, int B, int S, int d, int H,
+                                      float scale_log2, int64_t N, int seg, float* __restrict__ partials) {
+  const int dh = d / H;
+  const int h = blockIdx.y;
+  const int64_t seg_begin = int64_t(blockIdx.x) * seg;
+  const int64_t seg_end = (seg_begin + seg < N) ? seg_begin + seg : N;
+  int user = find_user(offsets, B, seg_begin);
+  int64_t pos = seg_begin;
+  Piece pc;
+  while (next_piece(offsets, B, seg_end, user, pos, pc)) {
+    const int64_t slot = int64_t(blockIdx.x) + pc.user;
+    for (int i = threadIdx.x; i < S; i += blockDim.x) {
+      float q[kMaxDh], o[kMaxDh];
+      const T* qrow = Q + q_user_stride * pc.user + int64_t(i) * d + h * dh;
+      for (int t = 0; t < kMaxDh; ++t) {
+        q[t] = t < dh ? to_f32(qrow[t]) * scale_log2 : 0.f;
+        o[t] = 0.f;
+      }
+      float m = -INFINITY, l = 0.f;
+      for (int64_t j = pc.begin; j < pc.end; ++j) {
+        const float* kr = K + j * d + h * dh;
+        const float* vr = V + j * d + h * dh;
+        float s = 0.f;
+        for (int t = 0; t < kMaxDh; ++t)
+          if (t < dh) s = fmaf(q[t], kr[t], s);
+        float mn = fmaxf(m, s);
+        float alpha = exp2f(m - mn);  // exp2(-inf) = 0 on the first item
+        float p = exp2f(s - mn);
+        l = l * alpha + p;
+        for (int t = 0; t < kMaxDh; ++t)
+          if (t < dh) o[t] = fmaf(o[t], alpha, p * vr[t]);
+        m = mn;
+      }
+      float* dst = partials + ((slot * H + h) * S + i) * (dh + 2);
+      for (int t = 0; t < kMaxDh; ++t)
+        if (t < dh) dst[t] = o[t];
+      dst[dh] = l;
+      dst[dh + 1] = m;
+    }
+  }
+}
+
+// ------------------------------------------------------- stage 1: merge
+// Combines a user's partial slots in ascending segment order:
+//   m = max m_c,  l = sum l_c 2^(m_c - m),  O = sum O_c 2^(m_c - m),  out = O / l.
+// grid (B, H); threads stride over (query, channel).
+template <typename T>
+__global__ void merge_kernel(const float* __restrict__ partials, const int64_t* __restrict__ offsets,
+                             int S, int d, int H, int seg, int64_t G, T* __restrict__ out) {
+  const int dh = d / H;
+  const int b = blockIdx.x, h = blockIdx.y;
+  const int64_t begin = offsets[b], end = offsets[b + 1];
+  T* dst = out + int64_t(b) * S * d + h * dh;
+  if (end <= begin) {
+    for (int e = threadIdx.x; e < S * dh; e += blockDim.x) store_as(dst + int64_t(e / dh) * d + (e % dh), 0.f);
+    return;
+  }
+  int64_t g0 = begin / seg, g1 = (end - 1) / seg;
+  if (g0 < 0) g0 = 0;
+  if (g1 > G - 1) g1 = G - 1;
+  for (int e = threadIdx.x; e < S * dh; e += blockDim.x) {
+    const int i = e / dh, t = e % dh;
+    float m = -INFINITY;
+    for (int64_t g = g0; g <= g1; ++g) {
+      const float* p = partials + (((g + b) * H + h) * S + i) * (dh + 2);
+      m = fmaxf(m, p[dh + 1]);
+    }
+    float l = 0.f, o = 0.f;
+    for (int64_t g = g0; g <= g1; ++g) {
+      const float* p = partials + (((g + b) * H + h) * S + i) * (dh + 2);
+      float w = exp2f(p[dh + 1] - m);
+      l = fmaf(p[dh], w, l);
+      o = fmaf(p[t], w, o);
+    }
+    store_as(dst + int64_t(i) * d + t, o / l);
+  }
+}
+
+static size_t generic_partials_bytes(const vista_summarize_desc& d, int seg) {
+  int64_t G = (d.total_items + seg - 1) / seg;
+  int dh = d.d / d.H;
+  return size_t(G + d.B) * d.H * d.S * (dh + 2) * sizeof(float);
+}
+
+static size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
+
+size_t generic_summarize_workspace(const vista_summarize_desc& d, int seg) {
+  return kHeaderBytes + align256(generic_partials_bytes(d, seg)) +
+         2 * align256(size_t(d.total_items) * d.d * sizeof(float));
+}
+
+template <typename T>
+static vista_status generic_summarize_t(const SummarizeArgs& a) {
+  const vista_summarize_desc& d = a.desc;
+  const int64_t N = d.total_items;
+  float* partials = reinterpret_cast<float*>(a.workspace + kHeaderBytes);
+  float* K = reinterpret_cast<float*>(a.workspace + kHeaderBytes + align256(generic_partials_bytes(d, a.seg)));
+  float* V = K + align256(size_t(N) * d.d * sizeof(float)) / sizeof(float);
+  if (N > 0) {
+    int64_t total = N * d.d;
+    int64_t blocks = (total + 255) / 256;
+    if (blocks > 0x7FFFFFFF) return VISTA_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(project_kernel<T>, dim3(unsigned(blocks)), dim3(256), 0, a.stream,
+                       static_cast<const T*>(a.X), static_cast<const T*>(a.Wk), static_cast<const T*>(a.Wv),
+                       K, V, N, d.d);
+    VISTA_LAUNCH_CHECK();
+    hipLaunchKernelGGL(attend_history_kernel<T>, dim3(unsigned(a.G), d.H), dim3(64), 0, a.stream, K, V,
+                       static_cast<const T*>(a.Q), d.q_user_stride, a.offsets, d.B, d.S, d.d, d.H,
+                       a.scale_log2, N, a.seg, partials);
+    VISTA_LAUNCH_CHECK();
+  }
+  hipLaunchKernelGGL(merge_kernel<T>, dim3(d.B, d.H), dim3(256), 0, a.stream, partials, a.offsets, d.S, d.d,
+                     d.H, a.seg, a.G, static_cast<T*>(a.out));
+  VISTA_LAUNCH_CHECK();
+  return VISTA_OK;
+}
+
+vista_status generic_summarize(const SummarizeArgs& a) {
+  if (a.desc.d / a.desc.H > kMaxDh) return VISTA_ERR_UNSUPPORTED;
+  return a.desc.dtype == VISTA_BF16 ? generic_summarize_t<bf16_t>(a) : generic_summarize_t<float>(a);
+}
+
+// ------------------------------------------------------------------ stage 2
+// One thread per (user, candidate, head); keys = values = the user's summaries.
+template <typename T>
+__global__ void target_attend_kernel(const T* __restrict__ cand, const T* __restrict__ summ,
+                                     T* __restrict__ out, int64_t total, int C, int S, int d, int H,
+                                     float scale_log2) {
+  const int dh = d / H;
+  int64_t idx = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int h = int(idx % H);
+  const int64_t bc = idx / H;     // flat (user, candidate)
+  const int64_t b = bc / C;
+  const T* qrow = cand + bc * d + h * dh;
+  const T* Y = summ + b * S * d + h * dh;
+  float q[kMaxDh], o[kMaxDh];
+  for (int t = 0; t < kMaxDh; ++t) {
+    q[t] = t < dh ? to_f32(qrow[t]) * scale_log2 : 0.f;
+    o[t] = 0.f;
+  }
+  float m = -INFINITY, l = 0.f;
+  for (int j = 0; j < S; ++j) {
+    const T* y = Y + int64_t(j) * d;
+    float s = 0.f;
+    for (int t = 0; t < kMaxDh; ++t)
+      if (t < dh) s = fmaf(q[t], to_f32(y[t]), s);
+    float mn = fmaxf(m, s);
+    float alpha = exp2f(m - mn);
+    float p = exp2f(s - mn);
+    l = l * alpha + p;
+    for (int t = 0; t < kMaxDh; ++t)
+      if (t < dh) o[t] = fmaf(o[t], alpha, p * to_f32(y[t]));
+    m = mn;
+  }
+  T* dst = out + bc * d + h * dh;
+  const float inv = 1.f / l;
+  for (int t = 0; t < kMaxDh; ++t)
+    if (t < dh) store_as(dst + t, o[t] * inv);
+}
+
+vista_status generic_target_attend(const vista_attend_desc& d, float scale_log2, const void* cand,
+                                   const void* summ, void* out, hipStream_t s) {
+  if (d.d / d.H > kMaxDh) return VISTA_ERR_UNSUPPORTED;
+  int64_t total = int64_t(d.B) * d.C * d.H;
+  int64_t blocks = (total + 127) / 128;
+  if (blocks > 0x7FFFFFFF) return VISTA_ERR_UNSUPPORTED;
+  if (d.dtype == VISTA_BF16)
+    hipLaunchKernelGGL(target_attend_kernel<bf16_t>, dim3(unsigned(blocks)), dim3(128), 0, s,
+                       static_cast<const bf16_t*>(cand), static_cast<const bf16_t*>(summ),
+                       static_cast<bf16_t*>(out), total, d.C, d.S, d.d, d.H, scale_log2);
+  else
+    hipLaunchKernelGGL(target_attend_kernel<float>, dim3(unsigned(blocks)), dim3(128), 0, s,
+                       static_cast<const float*>(cand), static_cast<const float*>(summ),
+                       static_cast<float*>(out), total, d.C, d.S, d.d, d.H, scale_log2);
+  VISTA_LAUNCH_CHECK();
+  return VISTA_OK;
+}
+
+// ------------------------------------------------------- gated block
+// One workgroup per R rows: yhat and the gated hidden row live in LDS.
+constexpr int kFfnRows = 4;
+
+template <typename T>
+__global__ void sglu_ffn_kernel(const T* __restrict__ y, const T* __restrict__ Wg, const T* __restrict__ Wu,
+                                const T* __restrict__ Wo, T* __restrict__ out, int64_t rows, int d, int dff,
+                                float eps) {
+  extern __shared__ float lds[];
+  float* yh = lds;                    // [R][d]
+  float* hid = lds + kFfnRows * d;    // [R][dff]
+  __shared__ float inv_rms[kFfnRows];
+  const int64_t row0 = int64_t(blockIdx.x) * kFfnRows;
+  const int nrow = int(rows - row0 < kFfnRows ? rows - row0 : kFfnRows);
+  for (int e = threadIdx.x; e < kFfnRows * d; e += blockDim.x) {
+    int r = e / d, t = e % d;
+    yh[e] = r < nrow ? to_f32(y[(row0 + r) * d + t]) : 0.f;
+  }
+  __syncthreads();
+  if (threadIdx.x < kFfnRows) {
+    float ss = 0.f;
+    for (int t = 0; t < d; ++t) ss = fmaf(yh[threadIdx.x * d + t], yh[threadIdx.x * d + t], ss);
+    inv_rms[threadIdx.x] = 1.f / sqrtf(ss / d + eps);
+  }
+  __syncthreads();
+  for (int e = threadIdx.x; e < kFfnRows * d; e += blockDim.x) yh[e] *= inv_rms[e / d];
+  __syncthreads();
+  for (int f = threadIdx.x; f < dff; f += blockDim.x) {
+    float g[kFfnRows], u[kFfnRows];
+    for (int r = 0; r < kFfnRows; ++r) g[r] = u[r] = 0.f;
+    for (int t = 0; t < d; ++t) {
+      float wg = to_f32(Wg[int64_t(t) * dff + f]), wu = to_f32(Wu[int64_t(t) * dff + f]);
+      for (int r = 0; r < kFfnRows; ++r) {
+        g[r] = fmaf(yh[r * d + t], wg, g[r]);
+        u[r] = fmaf(yh[r * d + t], wu, u[r]);
+      }
+    }
+    for (int r = 0; r < kFfnRows; ++r) hid[r * dff + f] = g[r] / (1.f + expf(-g[r])) * u[r];
+  }
+  __syncthreads();
+  for (int c = threadIdx.x; c < d; c += blockDim.x) {
+    float acc[kFfnRows];
+    for (int r = 0; r < kFfnRows; ++r) acc[r] = 0.f;
+    for (int f = 0; f < dff; ++f) {
+      float w = to_f32(Wo[int64_t(f) * d + c]);
+      for (int r = 0; r < kFfnRows; ++r) acc[r] = fmaf(hid[r * dff + f], w, acc[r]);
+    }
+    for (int r = 0; r < nrow; ++r) store_as(out + (row0 + r) * d + c, acc[r]);
+  }
+}
+
+vista_status generic_sglu_ffn(const vista_ffn_desc& d, float eps, const void* y, const void* Wg,
+                              const void* Wu, const void* Wo, void* out, hipStream_t s) {
+  int64_t blocks = (d.rows + kFfnRows - 1) / kFfnRows;
+  if (blocks > 0x7FFFFFFF) return VISTA_ERR_UNSUPPORTED;
+  size_t lds = size_t(kFfnRows) * (d.d + d.d_ff) * sizeof(float);
+  if (d.dtype == VISTA_BF16)
+    hipLaunchKernelGGL(sglu_ffn_kernel<bf16_t>, dim3(unsigned(blocks)), dim3(256), lds, s,
+                       static_cast<const bf16_t*>(y), static_cast<const bf16_t*>(Wg),
+                       static_cast<const bf16_t*>(Wu), static_cast<const bf16_t*>(Wo),
+                       static_cast<bf16_t*>(out), d.rows, d.d, d.d_ff, eps);
+  else
+    hipLaunchKernelGGL(sglu_ffn_kernel<float>, dim3(unsigned(blocks)), dim3(256), lds, s,
+                       static_cast<const float*>(y), static_cast<const float*>(Wg),
+                       static_cast<const float*>(Wu), static_cast<const float*>(Wo),
+                       static_cast<float*>(out), d.rows, d.d, d.d_ff, eps);
+  VISTA_LAUNCH_CHECK();
+  return VISTA_OK;
+}
+
+}  // namespace vista

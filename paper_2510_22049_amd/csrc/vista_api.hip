@@ -1,0 +1,135 @@
+// C ABI of libvista: argument validation, schedule resolution and dispatch to
+// the kernel families.  No allocation, no synchronisation, no global state.
+#include <math.h>
+
+#include "common.hpp"
+
+using namespace vista;
+
+namespace {
+
+bool dtype_ok(int32_t t) { return t == VISTA_F32 || t == VISTA_BF16; }
+
+// Shape rules of vista_summarize that do not depend on pointers.
+vista_status check_summarize_desc(const vista_summarize_desc* d) {
+  if (!d) return VISTA_ERR_NULL;
+  if (d->B <= 0 || d->S <= 0 || d->d <= 0 || d->H <= 0 || d->total_items < 0) return VISTA_ERR_SHAPE;
+  if (d->d % d->H != 0) return VISTA_ERR_SHAPE;
+  if (d->q_user_stride != 0 && d->q_user_stride != int64_t(d->S) * d->d) return VISTA_ERR_SHAPE;
+  if (d->segment_items < 0 || d->segment_items % 32 != 0) return VISTA_ERR_SHAPE;
+  if (!(d->scale >= 0.f) || isinf(d->scale)) return VISTA_ERR_SHAPE;
+  if (!dtype_ok(d->dtype) || d->attn != VISTA_ATTN_SOFTMAX) return VISTA_ERR_UNSUPPORTED;
+  if (d->S > 512 || d->d > 512 || d->d / d->H > 64) return VISTA_ERR_UNSUPPORTED;
+  return VISTA_OK;
+}
+
+// Default segment size: a function of N alone (about 512 segments, at least
+// 256 items, a multiple of 32), so the schedule never depends on the device.
+int32_t resolve_segment(const vista_summarize_desc* d) {
+  if (d->segment_items > 0) return d->segment_items;
+  int64_t s = (d->total_items + 511) / 512;
+  s = (s + 31) / 32 * 32;
+  if (s < 256) s = 256;
+  if (s > (1 << 30)) s = 1 << 30;
+  return int32_t(s);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* vista_status_string(int status) {
+  switch (status) {
+    case VISTA_OK: return "VISTA_OK";
+    case VISTA_ERR_NULL: return "VISTA_ERR_NULL: a required pointer is NULL";
+    case VISTA_ERR_SHAPE: return "VISTA_ERR_SHAPE: inconsistent or non-positive sizes";
+    case VISTA_ERR_OFFSETS: return "VISTA_ERR_OFFSETS: offsets must start at 0, not decrease, end at total_items";
+    case VISTA_ERR_UNSUPPORTED: return "VISTA_ERR_UNSUPPORTED: dtype, head width or S outside the supported set";
+    case VISTA_ERR_WORKSPACE: return "VISTA_ERR_WORKSPACE: workspace NULL, misaligned or too small";
+    case VISTA_ERR_HIP: return "VISTA_ERR_HIP: a kernel launch failed";
+    default: return "unknown vista status";
+  }
+}
+
+int32_t vista_summarize_segment_items(const vista_summarize_desc* desc) {
+  if (check_summarize_desc(desc) != VISTA_OK) return 0;
+  return resolve_segment(desc);
+}
+
+size_t vista_summarize_workspace_bytes(const vista_summarize_desc* desc) {
+  if (check_summarize_desc(desc) != VISTA_OK) return 0;
+  int seg = resolve_segment(desc);
+  return mfma_summarize_supported(*desc) ? mfma_summarize_workspace(*desc, seg)
+                                         : generic_summarize_workspace(*desc, seg);
+}
+
+vista_status vista_summarize(const vista_summarize_desc* desc, const void* history_emb,
+                             const int64_t* offsets, const int64_t* offsets_host,
+                             const void* virtual_queries, const void* W_k, const void* W_v, void* out,
+                             void* workspace, size_t workspace_bytes, void* hip_stream) {
+  vista_status st = check_summarize_desc(desc);
+  if (st != VISTA_OK) return st;
+  if (!offsets || !virtual_queries || !W_k || !W_v || !out) return VISTA_ERR_NULL;
+  if (desc->total_items > 0 && !history_emb) return VISTA_ERR_NULL;
+  if (offsets_host) {
+    if (offsets_host[0] != 0 || offsets_host[desc->B] != desc->total_items) return VISTA_ERR_OFFSETS;
+    for (int b = 0; b < desc->B; ++b)
+      if (offsets_host[b + 1] < offsets_host[b]) return VISTA_ERR_OFFSETS;
+  }
+  const size_t need = vista_summarize_workspace_bytes(desc);
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0 || workspace_bytes < need)
+    return VISTA_ERR_WORKSPACE;
+
+  SummarizeArgs a;
+  a.desc = *desc;
+  a.seg = resolve_segment(desc);
+  a.G = (desc->total_items + a.seg - 1) / a.seg;
+  if (a.G + desc->B > 0x7FFFFFFF) return VISTA_ERR_UNSUPPORTED;
+  const float scale = desc->scale > 0.f ? desc->scale : 1.f / sqrtf(float(desc->d / desc->H));
+  a.scale_log2 = scale * kLog2e;
+  a.X = history_emb;
+  a.offsets = offsets;
+  a.Q = virtual_queries;
+  a.Wk = W_k;
+  a.Wv = W_v;
+  a.out = out;
+  a.workspace = static_cast<char*>(workspace);
+  a.stream = static_cast<hipStream_t>(hip_stream);
+
+  launch_check_offsets(offsets, desc->B, desc->total_items, reinterpret_cast<int*>(workspace), a.stream);
+  if (hipGetLastError() != hipSuccess) return VISTA_ERR_HIP;
+  return mfma_summarize_supported(*desc) ? mfma_summarize(a) : generic_summarize(a);
+}
+
+vista_status vista_target_attend(const vista_attend_desc* desc, const void* candidates,
+                                 const void* summaries, void* out, void* hip_stream) {
+  if (!desc) return VISTA_ERR_NULL;
+  if (desc->B <= 0 || desc->C <= 0 || desc->S <= 0 || desc->d <= 0 || desc->H <= 0) return VISTA_ERR_SHAPE;
+  if (desc->d % desc->H != 0) return VISTA_ERR_SHAPE;
+  if (!(desc->scale >= 0.f) || isinf(desc->scale)) return VISTA_ERR_SHAPE;
+  if (!dtype_ok(desc->dtype)) return VISTA_ERR_UNSUPPORTED;
+  if (desc->S > 512 || desc->d / desc->H > 64) return VISTA_ERR_UNSUPPORTED;
+  if (!candidates || !summaries || !out) return VISTA_ERR_NULL;
+  const float scale = desc->scale > 0.f ? desc->scale : 1.f / sqrtf(float(desc->d / desc->H));
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  if (mfma_target_attend_supported(*desc))
+    return mfma_target_attend(*desc, scale * kLog2e, candidates, summaries, out, s);
+  return generic_target_attend(*desc, scale * kLog2e, candidates, summaries, out, s);
+}
+
+vista_status vista_sglu_ffn(const vista_ffn_desc* desc, const void* y, const void* W_g, const void* W_u,
+                            const void* W_o, void* out, void* hip_stream) {
+  if (!desc) return VISTA_ERR_NULL;
+  if (desc->rows <= 0 || desc->d <= 0 || desc->d_ff <= 0) return VISTA_ERR_SHAPE;
+  if (!(desc->eps >= 0.f) || isinf(desc->eps)) return VISTA_ERR_SHAPE;
+  if (!dtype_ok(desc->dtype)) return VISTA_ERR_UNSUPPORTED;
+  if (desc->d > 512 || desc->d_ff > 1024 || desc->d % 32 != 0 || desc->d_ff % 32 != 0)
+    return VISTA_ERR_UNSUPPORTED;
+  if (!y || !W_g || !W_u || !W_o || !out) return VISTA_ERR_NULL;
+  const float eps = desc->eps > 0.f ? desc->eps : 1e-6f;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  if (mfma_sglu_ffn_supported(*desc)) return mfma_sglu_ffn(*desc, eps, y, W_g, W_u, W_o, out, s);
+  return generic_sglu_ffn(*desc, eps, y, W_g, W_u, W_o, out, s);
+}
+
+}  // extern "C"

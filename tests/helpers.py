@@ -1,0 +1,35 @@
+"""Test plumbing shared by the GPU parity tests (no arithmetic of the method)."""
+import numpy as np
+import torch
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}     # max error per output block relative to the block's max |value|
+
+
+def torch_dtype(name):
+    return torch.float32 if name == "f32" else torch.bfloat16
+
+
+def dev(x: np.ndarray, dtype: str) -> torch.Tensor:
+    """Storage-rounded fp32 host values -> device tensor of the storage dtype (exact)."""
+    return torch.from_numpy(np.ascontiguousarray(x)).to("cuda").to(torch_dtype(dtype))
+
+
+def host64(t: torch.Tensor) -> np.ndarray:
+    return t.detach().to(torch.float32).cpu().numpy().astype(np.float64)
+
+
+def block_errors(got: np.ndarray, want: np.ndarray) -> np.ndarray:
+    """max |got - want| / max |want| over each leading-index block (one user)."""
+    g = got.reshape(got.shape[0], -1)
+    w = want.reshape(want.shape[0], -1)
+    den = np.abs(w).max(axis=1)
+    den = np.where(den == 0, 1.0, den)
+    return np.abs(g - w).max(axis=1) / den
+
+
+def assert_blocks_close(got, want, dtype, what=""):
+    assert np.all(np.isfinite(got)), f"{what}: non-finite output"
+    err = block_errors(got, want)
+    worst = int(err.argmax())
+    assert err[worst] <= TOL[dtype], f"{what}: block {worst} error {err[worst]:.3e} > {TOL[dtype]:.0e}"
+    return float(err.max())

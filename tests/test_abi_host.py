@@ -1,0 +1,93 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol the
+header declares, and rejects bad descriptors and offsets before any launch."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2510_22049_amd import binding as V
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "vista.h")).read()
+    declared = set(re.findall(r"\b(vista_[a-z_]+)\s*\(", header))
+    assert declared == set(V.EXPORTS)
+    L = V.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+def test_status_strings():
+    L = V.lib()
+    assert L.vista_status_string(0) == b"VISTA_OK"
+    for code in range(1, 7):
+        assert L.vista_status_string(code).startswith(b"VISTA_ERR_")
+    assert b"unknown" in L.vista_status_string(99)
+
+
+def desc(**kw):
+    base = dict(B=2, S=16, d=64, H=1, dtype=V.VISTA_F32, total_items=100)
+    base.update(kw)
+    return V.summarize_desc(**base)
+
+
+def test_segment_default_is_a_function_of_total_items_only():
+    assert V.vista_summarize_segment_items(desc(total_items=1024)) == 256
+    assert V.vista_summarize_segment_items(desc(total_items=768597, B=64)) == 1504
+    assert V.vista_summarize_segment_items(desc(total_items=8_000_000, B=8)) == 15648
+    assert V.vista_summarize_segment_items(desc(segment_items=64)) == 64
+    assert V.vista_summarize_segment_items(desc(segment_items=48)) == 0      # not a multiple of 32
+    assert V.vista_summarize_workspace_bytes(desc()) > 0
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(B=0), V.VISTA_ERR_SHAPE),
+    (dict(d=66, H=4), V.VISTA_ERR_SHAPE),
+    (dict(S=513), V.VISTA_ERR_UNSUPPORTED),
+    (dict(d=512, H=4), V.VISTA_ERR_UNSUPPORTED),
+    (dict(dtype=7), V.VISTA_ERR_UNSUPPORTED),
+    (dict(scale=-1.0), V.VISTA_ERR_SHAPE),
+])
+def test_summarize_rejects_bad_descriptors(kw, code):
+    d = desc(**kw)
+    one = C.c_void_p(256)                  # never dereferenced: the descriptor fails first
+    st = V.lib().vista_summarize(C.byref(d), one, one, None, one, one, one, one, one, 1 << 30, None)
+    assert st == code
+    assert V.vista_summarize_workspace_bytes(d) == 0
+
+
+def test_summarize_rejects_null_bad_offsets_and_small_workspace():
+    d = desc()
+    L = V.lib()
+    one = C.c_void_p(256)
+    assert L.vista_summarize(C.byref(d), one, None, None, one, one, one, one, one, 1 << 30, None) == V.VISTA_ERR_NULL
+    assert L.vista_summarize(None, one, one, None, one, one, one, one, one, 1 << 30, None) == V.VISTA_ERR_NULL
+    for bad in ([1, 50, 100], [0, 60, 50], [0, 50, 99]):
+        off = np.array(bad, dtype=np.int64)
+        st = L.vista_summarize(C.byref(d), one, one, off.ctypes.data, one, one, one, one, one, 1 << 30, None)
+        assert st == V.VISTA_ERR_OFFSETS
+    good = np.array([0, 50, 100], dtype=np.int64)
+    need = V.vista_summarize_workspace_bytes(d)
+    args = (C.byref(d), one, one, good.ctypes.data, one, one, one, one)
+    assert L.vista_summarize(*args, one, need - 1, None) == V.VISTA_ERR_WORKSPACE
+    assert L.vista_summarize(*args, None, need, None) == V.VISTA_ERR_WORKSPACE
+    assert L.vista_summarize(*args, C.c_void_p(264), need, None) == V.VISTA_ERR_WORKSPACE   # misaligned
+
+
+def test_attend_and_ffn_reject_bad_arguments():
+    L = V.lib()
+    one = C.c_void_p(256)
+    a = V.AttendDesc(B=1, C=4, S=8, d=64, H=3, dtype=V.VISTA_F32, scale=0.0)
+    assert L.vista_target_attend(C.byref(a), one, one, one, None) == V.VISTA_ERR_SHAPE
+    a = V.AttendDesc(B=1, C=4, S=1024, d=64, H=1, dtype=V.VISTA_F32, scale=0.0)
+    assert L.vista_target_attend(C.byref(a), one, one, one, None) == V.VISTA_ERR_UNSUPPORTED
+    a = V.AttendDesc(B=1, C=4, S=8, d=64, H=1, dtype=V.VISTA_F32, scale=0.0)
+    assert L.vista_target_attend(C.byref(a), None, one, one, None) == V.VISTA_ERR_NULL
+    f = V.FfnDesc(rows=4, d=48, d_ff=64, dtype=V.VISTA_BF16, eps=0.0)
+    assert L.vista_sglu_ffn(C.byref(f), one, one, one, one, one, None) == V.VISTA_ERR_UNSUPPORTED
+    f = V.FfnDesc(rows=0, d=64, d_ff=64, dtype=V.VISTA_BF16, eps=0.0)
+    assert L.vista_sglu_ffn(C.byref(f), one, one, one, one, one, None) == V.VISTA_ERR_SHAPE
