@@ -34,11 +34,20 @@ constexpr int kHeaderBytes = 256;  // workspace header: int32 device status at b
 // intersections of the segment with consecutive users.  Every row handed to a
 // caller lies inside the segment, hence inside [0, N), whatever offsets hold.
 // ---------------------------------------------------------------------------
+// offsets[] entries are read at workgroup-uniform addresses; telling the compiler
+// so keeps the whole piece walk (and everything derived from it) in scalar registers.
+__device__ __forceinline__ int64_t load_uniform(const int64_t* p) {
+  const int64_t v = *p;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane(uint32_t(uint64_t(v)));
+  const uint32_t hi = __builtin_amdgcn_readfirstlane(uint32_t(uint64_t(v) >> 32));
+  return int64_t((uint64_t(hi) << 32) | lo);
+}
+
 __device__ __forceinline__ int find_user(const int64_t* __restrict__ offsets, int B, int64_t row) {
   int lo = 0, hi = B;  // invariant: offsets[lo] <= row (offsets[0] = 0), answer in [lo, hi)
   while (hi - lo > 1) {
     int mid = (lo + hi) >> 1;
-    if (offsets[mid] <= row) lo = mid; else hi = mid;
+    if (load_uniform(offsets + mid) <= row) lo = mid; else hi = mid;
   }
   return lo;
 }
@@ -53,7 +62,7 @@ struct Piece {
 __device__ __forceinline__ bool next_piece(const int64_t* __restrict__ offsets, int B, int64_t seg_end,
                                            int& user, int64_t& pos, Piece& out) {
   while (pos < seg_end && user < B) {
-    int64_t uend = offsets[user + 1];
+    int64_t uend = load_uniform(offsets + user + 1);
     if (uend > pos) {
       int64_t e = uend < seg_end ? uend : seg_end;
       out.user = user;
