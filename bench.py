@@ -1,0 +1,180 @@
+#!/usr/bin/env python3
+"""Benchmark of the VISTA hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline]
+
+One step = one pass of the hot path over one synthetic batch:
+  stage 1  vista_summarize on the jagged-batch workload (64 users, lognormal
+           lengths with median 8k clipped to [1k, 100k], d=128, 4 heads, S=256, bf16);
+  stage 2  vista_target_attend on the serving workload (1024 users x 512
+           candidates over S=256 cached bf16 summaries, d=128, 4 heads).
+The headline `value` is stage-1 history items summarized per second; stage 2's
+candidate scores per second are reported in the same line under "stage2".
+Inputs are resident in HBM before the timed region; times come from HIP events
+recorded on the stream the kernels are launched on.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import numpy as np
+import torch
+
+from paper_2510_22049_amd import binding as V
+from paper_2510_22049_amd import inputs as I
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+
+
+def bf16_dev(x: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(x).cuda().to(torch.bfloat16)
+
+
+def time_steps(fn, steps: int, warmup: int) -> float:
+    """Milliseconds per step over exactly `steps` launches, HIP events on the launch stream."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    s = torch.cuda.current_stream()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(s)
+    for _ in range(steps):
+        fn()
+    e1.record(s)
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / steps
+
+
+def stage1_workload(sets: int):
+    c = I.CONFIGS[2]
+    lens = I.lengths(c)
+    off = I.offsets_from_lengths(lens)
+    N = int(off[-1])
+    Q, Wk, Wv = I.virtual_queries(c), I.projection(c, "W_k"), I.projection(c, "W_v")
+    X = I.history(c, lens)
+    dev = dict(off=torch.from_numpy(off).cuda(), off_host=torch.from_numpy(off), Q=bf16_dev(Q),
+               Wk=bf16_dev(Wk), Wv=bf16_dev(Wv))
+    # distinct copies of the history so consecutive steps do not re-read a cache-resident buffer
+    xs = [bf16_dev(X)]
+    for _ in range(sets - 1):
+        xs.append(xs[0].clone())
+    outs = [torch.empty((c.B, c.S, c.d), device="cuda", dtype=torch.bfloat16) for _ in range(sets)]
+    desc = V.summarize_desc(c.B, c.S, c.d, c.H, V.VISTA_BF16, N)
+    ws = torch.empty(V.vista_summarize_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+    host = dict(X=X, off=off, Q=Q, Wk=Wk, Wv=Wv, lens=lens)
+    return c, N, dev, xs, outs, ws, host
+
+
+def stage2_workload(sets: int):
+    c = I.CONFIGS[4]
+    g = torch.Generator(device="cuda")
+    g.manual_seed(0)
+    cands, summs, outs = [], [], []
+    for _ in range(sets):
+        cands.append(torch.randn((c.B, c.C, c.d), device="cuda", generator=g).to(torch.bfloat16))
+        summs.append(torch.randn((c.B, c.S, c.d), device="cuda", generator=g).to(torch.bfloat16))
+        outs.append(torch.empty((c.B, c.C, c.d), device="cuda", dtype=torch.bfloat16))
+    return c, cands, summs, outs
+
+
+def cpu_baseline(host, c, budget_s: float = 12.0):
+    """The numpy oracle, as it stands, on a bounded sample of the stage-1 workload."""
+    from oracle import vista_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    order = np.argsort(host["lens"])            # shortest users first so the sample is bounded
+    items, t0, used = 0, time.perf_counter(), []
+    for b in order:
+        lo, hi = host["off"][b], host["off"][b + 1]
+        O.summarize(host["X"][lo:hi], [0, hi - lo], host["Q"], host["Wk"], host["Wv"], c.H)
+        items += int(hi - lo)
+        used.append(int(b))
+        if time.perf_counter() - t0 > budget_s:
+            break
+    dt = time.perf_counter() - t0
+    return {"value": items / dt, "unit": "items/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"stage 1, {len(used)} shortest of 64 users of the jagged-batch workload, "
+                      f"{items} items in {dt:.1f} s (fp64 numpy)"}
+
+
+def main() -> None:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--segment-items", type=int, default=0)
+    a = ap.parse_args()
+    if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    V.lib()
+    torch.cuda.set_device(0)
+    SETS = 4
+
+    # ------------------------------------------------------------- stage 1
+    c1, N, dev, xs, outs, ws, host = stage1_workload(SETS)
+    it = {"i": 0}
+
+    def step1():
+        k = it["i"] % SETS
+        it["i"] += 1
+        V.vista_summarize(xs[k], dev["off"], dev["Q"], dev["Wk"], dev["Wv"], outs[k], H=c1.H,
+                          offsets_host=dev["off_host"], workspace=ws, segment_items=a.segment_items)
+
+    ms1 = time_steps(step1, a.steps, a.warmup)
+    items_per_s = N / (ms1 * 1e-3)
+    flop_item = 4 * c1.d * c1.d + 4 * c1.S * c1.d          # K,V projection + QK^T + PV, per item
+    tflops = flop_item * items_per_s / 1e12
+
+    # ------------------------------------------------------------- stage 2
+    c2, cands, summs, outs2 = stage2_workload(SETS)
+    jt = {"i": 0}
+
+    def step2():
+        k = jt["i"] % SETS
+        jt["i"] += 1
+        V.vista_target_attend(cands[k], summs[k], outs2[k], H=c2.H)
+
+    ms2 = time_steps(step2, a.steps, a.warmup)
+    cand_per_s = c2.B * c2.C / (ms2 * 1e-3)
+    bytes_cand = 2 * c2.d * 2 + c2.S * c2.d * 2 / c2.C       # candidate in + out + summaries amortised
+    gbs = bytes_cand * cand_per_s / 1e9
+
+    res = {
+        "metric": "history items summarized/sec (stage 1, S=256) + candidate scores/sec (stage 2)",
+        "value": items_per_s, "unit": "items/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": ms1, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "stage-1 jagged batch: 64 users, lognormal lengths (median 8k, [1k,100k]), "
+                               "d=128, 4 heads, S=256, bf16", "total_items": N,
+                   "segment_items": V.vista_summarize_segment_items(
+                       V.summarize_desc(c1.B, c1.S, c1.d, c1.H, V.VISTA_BF16, N, segment_items=a.segment_items))},
+        "roofline": {"bound": "mfma", "achieved": tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": tflops / PEAK_BF16_TFLOPS, "traffic": None,
+                     "kernel": "summarize_mfma_kernel<128,4,4>", "flop_per_item": flop_item,
+                     "note": "duration = whole vista_summarize call (offset check + main + merge kernels)"},
+        "stage2": {"value": cand_per_s, "unit": "candidate scores/s", "ms_per_step": ms2,
+                   "config": {"workload": "stage-2 serving: 1024 users x 512 candidates, S=256, d=128, 4 heads, bf16"},
+                   "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                "frac": gbs / PEAK_HBM_GBS, "traffic": None, "bytes_per_candidate": bytes_cand}},
+    }
+    if not a.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(host, c1)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

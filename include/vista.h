@@ -75,8 +75,10 @@ typedef struct {
  * device, so results are bitwise reproducible.
  *
  * vista_summarize_segment_items: the segment size the call will use
- * (desc->segment_items, or the default derived from total_items alone);
- * 0 if the descriptor is invalid.
+ * (desc->segment_items, or the default derived from total_items alone: the
+ * history is cut into 256 k equal segments, k the smallest count that keeps a
+ * segment at or below 8192 items; at least 256 items); 0 if the descriptor is
+ * invalid.
  */
 int32_t vista_summarize_segment_items(const vista_summarize_desc* desc);
 
@@ -108,7 +110,7 @@ size_t vista_summarize_workspace_bytes(const vista_summarize_desc* desc);
  *   out              device [B, S, d]     dtype (bf16: one round-to-nearest-even at the store)
  *   workspace        device, >= vista_summarize_workspace_bytes(desc), 256-byte aligned
  *
- * Supported: bf16 with d/H = 32, d in {128, 256}, S a multiple of 64 (MFMA path);
+ * Supported: bf16 with (d, H) = (128, 4) or (256, 8), S in {64, 128, 256, 512} (MFMA path);
  * any dtype with d/H <= 64, d <= 512, S <= 512 (plain fp32-ALU path).
  */
 vista_status vista_summarize(const vista_summarize_desc* desc,
@@ -145,8 +147,8 @@ typedef struct {
  *   summaries   device [B, S, d]  dtype
  *   out         device [B, C, d]  dtype
  *
- * Supported: bf16 with d/H = 32, S a multiple of 32 up to 512 (MFMA path);
- * any dtype with d/H <= 64, S <= 512 (plain path).  No workspace.
+ * Supported: bf16 with d/H = 32, H a multiple of 4, S a multiple of 32 up to 256
+ * (MFMA path); any dtype with d/H <= 64, S <= 512 (plain path).  No workspace.
  */
 vista_status vista_target_attend(const vista_attend_desc* desc,
                                  const void* candidates,

@@ -125,43 +125,40 @@ __device__ __forceinline__ void attend_block(const bf16x8& kop0, const bf16x8& k
   o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop1, p1.v, o, 0, 0, 0);
 }
 
-template <int D, int NQB, int HPW>
-__global__ __launch_bounds__(HPW * 128) void summarize_mfma_kernel(MfmaSummarizeParams p) {
+// Shared memory of one workgroup.
+template <int D, int HPW>
+struct SummarizeLds {
+  uint4 xbuf[2][(D / 8) * 33];        // X tile: [16-byte chunk][item + pad]
+  uint4 kvbuf[2][HPW][2][2][64];      // [buffer][head][K|V][half of the 16 registers][lane]
+  float knorm[2][HPW][64];            // squared norm of the scaled key rows (half per lane)
+};
+
+// Body of one wave; ROLE 0 forms K^T, ROLE 1 forms V.  The tile loop is
+// software-pipelined: while the wave attends over tile t (VALU-heavy) it also
+// issues the projection MFMAs of tile t+1, and the X rows of tiles t+2 / t+3
+// are on their way from HBM (registers) into the other LDS buffer.  One
+// LDS-only barrier per tile orders the two double-buffered exchanges.
+template <int D, int NQB, int HPW, int ROLE>
+__device__ __forceinline__ void summarize_wave(const MfmaSummarizeParams& p, SummarizeLds<D, HPW>& sm,
+                                               int64_t g, int h, int hl, int64_t seg_begin, int64_t seg_end) {
   constexpr int NT = HPW * 128;          // threads
   constexpr int CH = D / 8;              // 16-byte chunks per row
   constexpr int KS = D / 16;             // k-slices of the projection
   constexpr int CPT = kTile * CH / NT;   // X chunks a thread moves per tile
   static_assert(kTile * CH % NT == 0, "tile must split evenly over the workgroup");
-
-  __shared__ uint4 xbuf[2][CH * 33];            // [chunk][item + pad]
-  __shared__ uint4 kvbuf[2][HPW][2][2][64];     // [buffer][head][K|V][half of the 16 registers][lane]
-  __shared__ float knorm[2][HPW][64];
+  static_assert(KS % NQB == 0 || NQB % KS == 0, "projection slices are spread over the query blocks");
+  constexpr int KPB = (KS + NQB - 1) / NQB;   // projection k-slices issued per query block
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept scalar
-  const int hl = wave >> 1;
-  const int role = wave & 1;             // 0 forms K, 1 forms V
   const int hf = lane >> 5;
   const int l32 = lane & 31;
-
-  // XCD-aware block -> (segment, head group): the head groups of one segment
-  // share an XCD (and its L2) because their block ids differ by multiples of 8.
-  const int64_t id = blockIdx.x;
-  const int64_t grp = id / (8 * p.nhg);
-  const int idl = int(id - grp * 8 * p.nhg);
-  const int64_t g = grp * 8 + (idl & 7);
-  const int hg = idl >> 3;
-  const int h = hg * HPW + hl;
-  const int64_t seg_begin = g * p.seg;
-  if (seg_begin >= p.N) return;          // padding blocks of the last group (whole workgroup)
-  const int64_t seg_end = (seg_begin + p.seg < p.N) ? seg_begin + p.seg : p.N;
 
   // Projection weights of this wave's head, resident as MFMA operands:
   // element j of slice ks is W[16 ks + 8 hf + j][32 h + l32].
   bf16x8 wreg[KS];
   {
-    const uint16_t* W = role ? p.Wv : p.Wk;
+    const uint16_t* W = ROLE ? p.Wv : p.Wk;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       Pack8 t;
@@ -171,7 +168,7 @@ __global__ __launch_bounds__(HPW * 128) void summarize_mfma_kernel(MfmaSummarize
     }
   }
 
-  const int qbase = role * (NQB * 32);   // first query of this wave
+  const int qbase = ROLE * (NQB * 32);   // first query of this wave
   bf16x8 qop[NQB][2];
   float qmax2 = 0.f;
   auto load_queries = [&](int user) {
@@ -222,9 +219,11 @@ __global__ __launch_bounds__(HPW * 128) void summarize_mfma_kernel(MfmaSummarize
     }
     int mode = 0;  // 0 fresh, 1 constant reference 0, 2 running maximum
 
-    // X prefetch: registers hold the chunks of the next tile while this one is consumed.
-    uint4 xr[CPT];
-    auto fetch = [&](int t) {
+    // HBM -> registers -> LDS movement of X; two register sets alternate so a
+    // load has two tile periods to land.
+    uint4 xra[CPT], xrb[CPT];
+    auto fetch = [&](int t, uint4 (&xr)[CPT]) {
+      if (t >= ntiles) return;
       const int64_t r0 = pc.begin + int64_t(t) * kTile;
 #pragma unroll
       for (int k = 0; k < CPT; ++k) {
@@ -234,72 +233,51 @@ __global__ __launch_bounds__(HPW * 128) void summarize_mfma_kernel(MfmaSummarize
         xr[k] = *reinterpret_cast<const uint4*>(p.X + row * D + (cid % CH) * 8);
       }
     };
-    auto stash = [&](int buf) {
+    auto stash = [&](int t, int buf, const uint4 (&xr)[CPT]) {
+      if (t >= ntiles) return;
 #pragma unroll
       for (int k = 0; k < CPT; ++k) {
         const int cid = tid + k * NT;
-        xbuf[buf][(cid % CH) * 33 + cid / CH] = xr[k];
+        sm.xbuf[buf][(cid % CH) * 33 + cid / CH] = xr[k];
       }
     };
-
-    lds_barrier();   // previous piece's readers are done with both buffers
-    fetch(0);
-    stash(0);
-    if (ntiles > 1) fetch(1);
-    lds_barrier();
-
-    for (int t = 0; t < ntiles; ++t) {
-      const int buf = t & 1;
-      // ---- projection of this wave's head: K^T (role 0) or V (role 1)
-      f32x16 acc = {0};
-      if (role) {
+    // k-slices [ks0, ks1) of this wave's projection of the X tile in xbuf[buf]
+    auto project = [&](int buf, int ks0, int ks1, f32x16& acc) {
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          Pack8 x;
-          x.u = xbuf[buf][(2 * ks + hf) * 33 + l32];
-          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x.v, wreg[ks], acc, 0, 0, 0);
-        }
-      } else {
+      for (int ks = ks0; ks < ks1; ++ks) {
+        Pack8 x;
+        x.u = sm.xbuf[buf][(2 * ks + hf) * 33 + l32];
+        acc = ROLE ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(x.v, wreg[ks], acc, 0, 0, 0)
+                   : __builtin_amdgcn_mfma_f32_32x32x16_bf16(wreg[ks], x.v, acc, 0, 0, 0);
+      }
+    };
+    // hand the projected tile to the partner wave: bf16 operand halves (+ key norms)
+    auto publish = [&](int buf, const f32x16& acc) {
+      Pack8 r0, r1;
+      float n2 = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          Pack8 x;
-          x.u = xbuf[buf][(2 * ks + hf) * 33 + l32];
-          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wreg[ks], x.v, acc, 0, 0, 0);
-        }
+      for (int i = 0; i < 16; i += 2) {
+        const float a = ROLE ? acc[i] : acc[i] * p.c, b = ROLE ? acc[i + 1] : acc[i + 1] * p.c;
+        if (ROLE == 0) n2 = fmaf(a, a, fmaf(b, b, n2));
+        const uint32_t pk = cvt_pk_bf16(a, b);
+        if (i < 8) r0.w[i / 2] = pk; else r1.w[(i - 8) / 2] = pk;
       }
-      {
-        Pack8 r0, r1;
-        float n2 = 0.f;
-        const float mul = role ? 1.f : p.c;
-#pragma unroll
-        for (int i = 0; i < 16; i += 2) {
-          const float a = acc[i] * mul, b = acc[i + 1] * mul;
-          n2 = fmaf(a, a, fmaf(b, b, n2));
-          const uint32_t pk = cvt_pk_bf16(a, b);
-          if (i < 8) r0.w[i / 2] = pk; else r1.w[(i - 8) / 2] = pk;
-        }
-        kvbuf[buf][hl][role][0][lane] = r0.u;
-        kvbuf[buf][hl][role][1][lane] = r1.u;
-        if (role == 0) knorm[buf][hl][lane] = n2;
-      }
-      // ---- next X tile into the other buffer, then prefetch the one after
-      if (t + 1 < ntiles) {
-        stash(buf ^ 1);
-        if (t + 2 < ntiles) fetch(t + 2);
-      }
-      lds_barrier();
-
+      sm.kvbuf[buf][hl][ROLE][0][lane] = r0.u;
+      sm.kvbuf[buf][hl][ROLE][1][lane] = r1.u;
+      if (ROLE == 0) sm.knorm[buf][hl][lane] = n2;
+    };
+    // attention over tile t (operands in kvbuf[buf]) with the projection of tile t+1 woven in
+    auto tile = [&](int t, int buf) {
       Pack8 k0, k1, v0, v1;
-      k0.u = kvbuf[buf][hl][0][0][lane];
-      k1.u = kvbuf[buf][hl][0][1][lane];
-      v0.u = kvbuf[buf][hl][1][0][lane];
-      v1.u = kvbuf[buf][hl][1][1][lane];
-      const float kn2 = knorm[buf][hl][lane] + knorm[buf][hl][lane ^ 32];
+      k0.u = sm.kvbuf[buf][hl][0][0][lane];
+      k1.u = sm.kvbuf[buf][hl][0][1][lane];
+      v0.u = sm.kvbuf[buf][hl][1][0][lane];
+      v1.u = sm.kvbuf[buf][hl][1][1][lane];
+      const float kn2 = sm.knorm[buf][hl][lane] + sm.knorm[buf][hl][lane ^ 32];
       const bool unsafe = __builtin_amdgcn_ballot_w64(kn2 * qmax2 > kSafeBound2) != 0;
       const int64_t left = pc.end - (pc.begin + int64_t(t) * kTile);
       const int nvalid = left < kTile ? int(left) : kTile;
       const int nvl = nvalid - 4 * hf;
-
       const bool general = unsafe || mode == 2;
       if (general && mode == 0) {
 #pragma unroll
@@ -307,9 +285,41 @@ __global__ __launch_bounds__(HPW * 128) void summarize_mfma_kernel(MfmaSummarize
       }
       mode = general ? 2 : 1;
       const bool masked = nvalid < kTile;
+      const bool more = t + 1 < ntiles;
+      f32x16 acc = {0};
 #pragma unroll
-      for (int qb = 0; qb < NQB; ++qb)
+      for (int qb = 0; qb < NQB; ++qb) {
         attend_block(k0.v, k1.v, v0.v, v1.v, qop[qb][0], qop[qb][1], o[qb], l[qb], m[qb], general, masked, nvl);
+        if (more && qb * KPB < KS) project(buf ^ 1, qb * KPB, qb * KPB + KPB, acc);
+      }
+      if (more) publish(buf ^ 1, acc);
+    };
+
+    lds_barrier();   // every wave is done with the previous piece's buffers
+    fetch(0, xra);
+    fetch(1, xrb);
+    stash(0, 0, xra);
+    fetch(2, xra);
+    lds_barrier();
+    {
+      f32x16 acc = {0};
+      project(0, 0, KS, acc);
+      publish(0, acc);
+    }
+    stash(1, 1, xrb);
+    fetch(3, xrb);
+
+    for (int t = 0; t < ntiles; t += 2) {
+      lds_barrier();
+      tile(t, 0);
+      stash(t + 2, 0, xra);
+      fetch(t + 4, xra);
+      if (t + 1 < ntiles) {
+        lds_barrier();
+        tile(t + 1, 1);
+        stash(t + 3, 1, xrb);
+        fetch(t + 5, xrb);
+      }
     }
 
     // ---- partial record of this piece: slot = segment + user
@@ -324,6 +334,30 @@ __global__ __launch_bounds__(HPW * 128) void summarize_mfma_kernel(MfmaSummarize
       r[17 * 64] = m[qb];
     }
   }
+}
+
+template <int D, int NQB, int HPW>
+__global__ __launch_bounds__(HPW * 128, (HPW == 1 ? 2 : 1)) void summarize_mfma_kernel(MfmaSummarizeParams p) {
+  __shared__ SummarizeLds<D, HPW> sm;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform, kept scalar
+  const int hl = wave >> 1;
+
+  // XCD-aware block -> (segment, head group): the head groups of one segment
+  // share an XCD (and its L2) because their block ids differ by multiples of 8.
+  const int64_t id = blockIdx.x;
+  const int64_t grp = id / (8 * p.nhg);
+  const int idl = int(id - grp * 8 * p.nhg);
+  const int64_t g = grp * 8 + (idl & 7);
+  const int hg = idl >> 3;
+  const int h = hg * HPW + hl;
+  const int64_t seg_begin = g * p.seg;
+  if (seg_begin >= p.N) return;          // padding blocks of the last group (whole workgroup)
+  const int64_t seg_end = (seg_begin + p.seg < p.N) ? seg_begin + p.seg : p.N;
+  // Both roles run the same sequence of barriers; only the MFMA operand order differs.
+  if (wave & 1)
+    summarize_wave<D, NQB, HPW, 1>(p, sm, g, h, hl, seg_begin, seg_end);
+  else
+    summarize_wave<D, NQB, HPW, 0>(p, sm, g, h, hl, seg_begin, seg_end);
 }
 
 // Merge of a user's partial records, ascending segment order (fixed, so the
@@ -417,7 +451,14 @@ vista_status mfma_summarize(const SummarizeArgs& a) {
       switch (d.S) {
         case 64: launch_main<128, 1, 4>(p, a.G, a.stream); break;
         case 128: launch_main<128, 2, 4>(p, a.G, a.stream); break;
-        case 256: launch_main<128, 4, 4>(p, a.G, a.stream); break;
+        case 256:
+#ifdef EXP_HPW1
+          p.nhg = 4;
+          launch_main<128, 4, 1>(p, a.G, a.stream);
+#else
+          launch_main<128, 4, 4>(p, a.G, a.stream);
+#endif
+          break;
         default:
           p.nhg = 2;
           launch_main<128, 8, 2>(p, a.G, a.stream);

@@ -23,14 +23,17 @@ vista_status check_summarize_desc(const vista_summarize_desc* d) {
   return VISTA_OK;
 }
 
-// Default segment size: a function of N alone (about 512 segments, at least
-// 256 items, a multiple of 32), so the schedule never depends on the device.
+// Default segment size: a function of N alone (never of the device probed at
+// run time).  The history is cut into 256 k equal segments -- one workgroup per
+// compute unit of the target part and k rounds -- with k the smallest count
+// that keeps a segment at or below 8192 items; a multiple of 32, at least 256.
 int32_t resolve_segment(const vista_summarize_desc* d) {
   if (d->segment_items > 0) return d->segment_items;
-  int64_t s = (d->total_items + 511) / 512;
+  const int64_t N = d->total_items;
+  const int64_t k = (N + 256 * 8192 - 1) / (256 * 8192) > 0 ? (N + 256 * 8192 - 1) / (256 * 8192) : 1;
+  int64_t s = (N + 256 * k - 1) / (256 * k);
   s = (s + 31) / 32 * 32;
   if (s < 256) s = 256;
-  if (s > (1 << 30)) s = 1 << 30;
   return int32_t(s);
 }
 

@@ -37,8 +37,8 @@ def desc(**kw):
 
 def test_segment_default_is_a_function_of_total_items_only():
     assert V.vista_summarize_segment_items(desc(total_items=1024)) == 256
-    assert V.vista_summarize_segment_items(desc(total_items=768597, B=64)) == 1504
-    assert V.vista_summarize_segment_items(desc(total_items=8_000_000, B=8)) == 15648
+    assert V.vista_summarize_segment_items(desc(total_items=768597, B=64)) == 3008      # 256 segments
+    assert V.vista_summarize_segment_items(desc(total_items=8_000_000, B=8)) == 7840     # 4 x 256 segments
     assert V.vista_summarize_segment_items(desc(segment_items=64)) == 64
     assert V.vista_summarize_segment_items(desc(segment_items=48)) == 0      # not a multiple of 32
     assert V.vista_summarize_workspace_bytes(desc()) > 0
