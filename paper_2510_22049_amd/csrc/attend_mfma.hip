@@ -191,11 +191,7 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(AttendParams p) {
       Pack8 p0, p1;
 #pragma unroll
       for (int i = 0; i < 16; i += 2) {
-#ifdef EXP_NOEXP
-        const uint32_t pk = cvt_pk_bf16(sc[i], sc[i + 1]);
-#else
         const uint32_t pk = cvt_pk_bf16(__builtin_amdgcn_exp2f(sc[i]), __builtin_amdgcn_exp2f(sc[i + 1]));
-#endif
         l[(i / 2) & 3] = dot2_ones(pk, l[(i / 2) & 3]);
         if (i < 8) p0.w[i / 2] = pk; else p1.w[(i - 8) / 2] = pk;
       }
@@ -206,11 +202,7 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(AttendParams p) {
     lsum += __shfl_xor(lsum, 32, 64);
     const float inv = __builtin_amdgcn_rcpf(lsum);
     const int row = cb * 32 + l32;
-#ifdef EXP_NOSTORE
-    if (row < p.C && inv == 123.f) {
-#else
     if (row < p.C) {
-#endif
       uint16_t* dst = Ob + int64_t(row) * p.d + 32 * h + 4 * hf;
 #pragma unroll
       for (int g = 0; g < 4; ++g) {

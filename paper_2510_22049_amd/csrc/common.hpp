@@ -26,6 +26,8 @@ __device__ __forceinline__ void store_as(bf16_t* p, float v) { p->bits = f32_to_
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr int kHeaderBytes = 256;  // workspace header: int32 device status at byte 0
+// Workspace layout of vista_summarize: [header 256 B][seg_user int32[G], padded to 256 B][path-specific data]
+__host__ __device__ inline size_t plan_bytes(int64_t G) { return (size_t(G) * sizeof(int) + 255) & ~size_t(255); }
 
 // ---------------------------------------------------------------------------
 // Split-L piece walk (pure function of offsets and the segment size).
@@ -87,6 +89,7 @@ struct SummarizeArgs {
   vista_summarize_desc desc;
   int seg;            // resolved segment size
   int64_t G;          // segments
+  const int* seg_user; // [G] first user of each segment (written by the plan kernel)
   float scale_log2;   // scale * log2(e)
   const void* X;
   const int64_t* offsets;
@@ -116,6 +119,10 @@ bool mfma_sglu_ffn_supported(const vista_ffn_desc& d);
 vista_status mfma_sglu_ffn(const vista_ffn_desc& d, float eps, const void* y, const void* Wg,
                            const void* Wu, const void* Wo, void* out, hipStream_t s);
 
-void launch_check_offsets(const int64_t* offsets, int B, int64_t N, int* status, hipStream_t s);
+// Validates offsets on the device (status word) and records, for every segment,
+// the user that owns its first row (seg_user[g], int32), so that the main
+// kernels start their piece walk without a search.
+void launch_plan(const int64_t* offsets, int B, int64_t N, int seg, int64_t G, int* status, int* seg_user,
+                 hipStream_t s);
 
 }  // namespace vista

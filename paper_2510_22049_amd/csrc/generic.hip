@@ -10,26 +10,43 @@ constexpr int kMaxDh = 64;
 
 // ------------------------------------------------------------------ checks
 
-__global__ void check_offsets_kernel(const int64_t* __restrict__ offsets, int B, int64_t N,
-                                     int* __restrict__ status) {
-  // One block; thread 0 publishes the verdict after a block-wide OR.
-  __shared__ int bad;
-  if (threadIdx.x == 0) bad = 0;
-  __syncthreads();
-  int local = 0;
-  for (int b = threadIdx.x; b <= B; b += blockDim.x) {
-    int64_t o = offsets[b];
-    if (b == 0 && o != 0) local = 1;
-    if (b == B && o != N) local = 1;
-    if (b < B && offsets[b + 1] < o) local = 1;
+// Block 0 validates offsets and publishes the status word; every block takes a
+// grid-stride share of the segments and finds each one's first user by binary search.
+__global__ void plan_kernel(const int64_t* __restrict__ offsets, int B, int64_t N, int seg, int64_t G,
+                            int* __restrict__ status, int* __restrict__ seg_user) {
+  if (blockIdx.x == 0) {
+    __shared__ int bad;
+    if (threadIdx.x == 0) bad = 0;
+    __syncthreads();
+    int local = 0;
+    for (int64_t b = threadIdx.x; b <= B; b += blockDim.x) {
+      const int64_t o = offsets[b];
+      if (b == 0 && o != 0) local = 1;
+      if (b == B && o != N) local = 1;
+      if (b < B && offsets[b + 1] < o) local = 1;
+    }
+    if (local) atomicOr(&bad, 1);
+    __syncthreads();
+    if (threadIdx.x == 0) *status = bad ? int(VISTA_ERR_OFFSETS) : 0;
   }
-  if (local) atomicOr(&bad, 1);
-  __syncthreads();
-  if (threadIdx.x == 0) *status = bad ? int(VISTA_ERR_OFFSETS) : 0;
+  const int64_t stride = int64_t(gridDim.x) * blockDim.x;
+  for (int64_t g = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; g < G; g += stride) {
+    const int64_t row = g * seg;
+    int lo = 0, hi = B;               // last user whose first row is <= row
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (offsets[mid] <= row) lo = mid; else hi = mid;
+    }
+    seg_user[g] = lo;
+  }
 }
 
-void launch_check_offsets(const int64_t* offsets, int B, int64_t N, int* status, hipStream_t s) {
-  hipLaunchKernelGGL(check_offsets_kernel, dim3(1), dim3(256), 0, s, offsets, B, N, status);
+void launch_plan(const int64_t* offsets, int B, int64_t N, int seg, int64_t G, int* status, int* seg_user,
+                 hipStream_t s) {
+  int blocks = int((G + 255) / 256);
+  if (blocks < 1) blocks = 1;
+  if (blocks > 1024) blocks = 1024;
+  hipLaunchKernelGGL(plan_kernel, dim3(blocks), dim3(256), 0, s, offsets, B, N, seg, G, status, seg_user);
 }
 
 // -------------------------------------------------- stage 1: K/V projection
@@ -60,12 +77,13 @@ template <typename T>
 __global__ void attend_history_kernel(const float* __restrict__ K, const float* __restrict__ V,
                                       const T* __restrict__ Q, int64_t q_user_stride,
                                       const int64_t* __restrict__ offsets, int B, int S, int d, int H,
-                                      float scale_log2, int64_t N, int seg, float* __restrict__ partials) {
+                                      float scale_log2, int64_t N, int seg, const int* __restrict__ seg_user,
+                                      float* __restrict__ partials) {
   const int dh = d / H;
   const int h = blockIdx.y;
   const int64_t seg_begin = int64_t(blockIdx.x) * seg;
   const int64_t seg_end = (seg_begin + seg < N) ? seg_begin + seg : N;
-  int user = find_user(offsets, B, seg_begin);
+  int user = seg_user[blockIdx.x];
   int64_t pos = seg_begin;
   Piece pc;
   while (next_piece(offsets, B, seg_end, user, pos, pc)) {
@@ -146,7 +164,8 @@ static size_t generic_partials_bytes(const vista_summarize_desc& d, int seg) {
 static size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
 
 size_t generic_summarize_workspace(const vista_summarize_desc& d, int seg) {
-  return kHeaderBytes + align256(generic_partials_bytes(d, seg)) +
+  const int64_t G = (d.total_items + seg - 1) / seg;
+  return kHeaderBytes + plan_bytes(G) + align256(generic_partials_bytes(d, seg)) +
          2 * align256(size_t(d.total_items) * d.d * sizeof(float));
 }
 
@@ -154,8 +173,9 @@ template <typename T>
 static vista_status generic_summarize_t(const SummarizeArgs& a) {
   const vista_summarize_desc& d = a.desc;
   const int64_t N = d.total_items;
-  float* partials = reinterpret_cast<float*>(a.workspace + kHeaderBytes);
-  float* K = reinterpret_cast<float*>(a.workspace + kHeaderBytes + align256(generic_partials_bytes(d, a.seg)));
+  char* base = a.workspace + kHeaderBytes + plan_bytes(a.G);
+  float* partials = reinterpret_cast<float*>(base);
+  float* K = reinterpret_cast<float*>(base + align256(generic_partials_bytes(d, a.seg)));
   float* V = K + align256(size_t(N) * d.d * sizeof(float)) / sizeof(float);
   if (N > 0) {
     int64_t total = N * d.d;
@@ -167,7 +187,7 @@ static vista_status generic_summarize_t(const SummarizeArgs& a) {
     VISTA_LAUNCH_CHECK();
     hipLaunchKernelGGL(attend_history_kernel<T>, dim3(unsigned(a.G), d.H), dim3(64), 0, a.stream, K, V,
                        static_cast<const T*>(a.Q), d.q_user_stride, a.offsets, d.B, d.S, d.d, d.H,
-                       a.scale_log2, N, a.seg, partials);
+                       a.scale_log2, N, a.seg, a.seg_user, partials);
     VISTA_LAUNCH_CHECK();
   }
   hipLaunchKernelGGL(merge_kernel<T>, dim3(d.B, d.H), dim3(256), 0, a.stream, partials, a.offsets, d.S, d.d,

@@ -3,7 +3,7 @@
 // One workgroup streams one flat segment of the packed history for HPW heads.
 // Each head is served by a pair of waves.  Per tile of 32 items:
 //   1. the workgroup copies the X tile (32 x D bf16) from HBM into LDS once;
-//   2. wave "K" of a pair forms K_h^T = W_k,h^T X^T (scaled by scale*log2 e),
+//   2. wave "K" of a pair forms K_h^T = (scale*log2e W_k,h)^T X^T,
 //      wave "V" forms V_h = X W_v,h -- eight 32x32x16 MFMAs each for D = 128 --
 //      and both hand the bf16 result to their partner through LDS;
 //   3. each wave owns half of the S queries: for every block of 32 queries
@@ -39,6 +39,7 @@ constexpr int kRecFloats = kRecRows * 64;
 struct MfmaSummarizeParams {
   const uint16_t* X;
   const int64_t* offsets;
+  const int* seg_user;
   const uint16_t* Q;
   int64_t q_user_stride;
   const uint16_t* Wk;
@@ -67,6 +68,11 @@ __device__ __forceinline__ uint32_t cvt_pk_bf16(float a, float b) {
 __device__ __forceinline__ float dot2_ones(uint32_t pk, float acc) {
   const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
   return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk), ones, acc, false);
+}
+
+__device__ __forceinline__ float dot2_self(uint32_t pk, float acc) {
+  const bf16x2 v = __builtin_bit_cast(bf16x2, pk);
+  return __builtin_amdgcn_fdot2_f32_bf16(v, v, acc, false);
 }
 
 // LDS-only workgroup barrier: global loads in flight (the X prefetch) stay in flight.
@@ -125,18 +131,24 @@ __device__ __forceinline__ void attend_block(const bf16x8& kop0, const bf16x8& k
   o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop1, p1.v, o, 0, 0, 0);
 }
 
+template <int V>
+struct Int { static constexpr int value = V; };
+
+constexpr int kXBuf = 3;             // X tiles in LDS: one being projected, two on their way
+
 // Shared memory of one workgroup.
 template <int D, int HPW>
 struct SummarizeLds {
-  uint4 xbuf[2][(D / 8) * 33];        // X tile: [16-byte chunk][item + pad]
+  uint4 xbuf[kXBuf][(D / 8) * 32];    // X tiles: [16-byte chunk][item], filled by direct global->LDS loads
   uint4 kvbuf[2][HPW][2][2][64];      // [buffer][head][K|V][half of the 16 registers][lane]
   float knorm[2][HPW][64];            // squared norm of the scaled key rows (half per lane)
+  uint4 wop[HPW][2][D / 16][64];      // projection weights as MFMA operands: [head][K|V][k-slice][lane]
 };
 
 // Body of one wave; ROLE 0 forms K^T, ROLE 1 forms V.  The tile loop is
 // software-pipelined: while the wave attends over tile t (VALU-heavy) it also
-// issues the projection MFMAs of tile t+1, and the X rows of tiles t+2 / t+3
-// are on their way from HBM (registers) into the other LDS buffer.  One
+// issues the projection MFMAs of tile t+1, and the X rows of tiles t+2 / t+3 are
+// on their way from HBM (registers) into the LDS buffer tile t has vacated.  One
 // LDS-only barrier per tile orders the two double-buffered exchanges.
 template <int D, int NQB, int HPW, int ROLE>
 __device__ __forceinline__ void summarize_wave(const MfmaSummarizeParams& p, SummarizeLds<D, HPW>& sm,
@@ -154,36 +166,42 @@ __device__ __forceinline__ void summarize_wave(const MfmaSummarizeParams& p, Sum
   const int hf = lane >> 5;
   const int l32 = lane & 31;
 
-  // Projection weights of this wave's head, resident as MFMA operands:
-  // element j of slice ks is W[16 ks + 8 hf + j][32 h + l32].
-  bf16x8 wreg[KS];
+  // Projection weights of this wave's head as MFMA operands, parked in LDS (each
+  // wave reads back only what it wrote; they are off the critical path, so the
+  // registers go to the accumulators instead).  Element j of slice ks is
+  // W[16 ks + 8 hf + j][32 h + l32]; the key weights carry scale*log2(e), so the
+  // scores leave the MFMA in base-2 units.
   {
     const uint16_t* W = ROLE ? p.Wv : p.Wk;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       Pack8 t;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) t.h[j] = W[(16 * ks + 8 * hf + j) * D + 32 * h + l32];
-      wreg[ks] = t.v;
+      for (int j = 0; j < 8; ++j) {
+        const uint16_t w = W[(16 * ks + 8 * hf + j) * D + 32 * h + l32];
+        t.h[j] = ROLE ? w : f32_to_bf16_bits(__uint_as_float(uint32_t(w) << 16) * p.c);
+      }
+      sm.wop[hl][ROLE][ks][lane] = t.u;
     }
   }
 
   const int qbase = ROLE * (NQB * 32);   // first query of this wave
   bf16x8 qop[NQB][2];
   float qmax2 = 0.f;
-  auto load_queries = [&](int user) {
-    const uint16_t* Qb = p.Q + p.q_user_stride * user;
+  auto load_queries = [&](int user) __attribute__((always_inline)) {
+    const char* Qb = reinterpret_cast<const char*>(p.Q + p.q_user_stride * user + int64_t(qbase) * D + 32 * h);
+    const uint32_t qoff = uint32_t(l32) * (D * 2) + uint32_t(hf) * 8;
     float worst = 0.f;
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) {
-      const uint16_t* row = Qb + int64_t(qbase + qb * 32 + l32) * D + 32 * h;
+      const char* row = Qb + qb * 32 * D * 2;
       float n2 = 0.f;
 #pragma unroll
       for (int part = 0; part < 2; ++part) {
         Pack8 t;
         // dh index of element j: 16 part + 4 hf + 8 (j / 4) + j % 4 -> two runs of four
-        const uint2 a = *reinterpret_cast<const uint2*>(row + 16 * part + 4 * hf);
-        const uint2 b = *reinterpret_cast<const uint2*>(row + 16 * part + 4 * hf + 8);
+        const uint2 a = *reinterpret_cast<const uint2*>(row + 32 * part + qoff);
+        const uint2 b = *reinterpret_cast<const uint2*>(row + 32 * part + 16 + qoff);
         t.w[0] = a.x; t.w[1] = a.y; t.w[2] = b.x; t.w[3] = b.y;
         qop[qb][part] = t.v;
 #pragma unroll
@@ -201,15 +219,55 @@ __device__ __forceinline__ void summarize_wave(const MfmaSummarizeParams& p, Sum
   };
   if (p.q_user_stride == 0) load_queries(0);
 
-  int user = find_user(p.offsets, p.B, seg_begin);
-  int64_t pos = seg_begin;
-  Piece pc;
-  while (next_piece(p.offsets, p.B, seg_end, user, pos, pc)) {
-    if (p.q_user_stride != 0) load_queries(pc.user);
-    const int ntiles = int((pc.end - pc.begin + kTile - 1) / kTile);
+  // ---- the segment as one stream of tiles.  A tile never spans two users; a
+  // cursor walks the pieces of the segment (scalar state, offsets read through
+  // uniform loads).  `ca` names the tile being attended over, `cf` runs three
+  // tiles ahead and names the tile whose rows are requested from HBM.  When a
+  // cursor runs off the segment it stays on its last tile (still in bounds).
+  struct Cursor {
+    int wuser;        // piece walk: next user to look at
+    int64_t wpos;     // piece walk: next flat row (= end of the current piece)
+    int user;         // user of the current piece
+    int64_t row;      // first row of the current tile
+    int tiles_left;   // tiles of the current piece not yet passed, this one included
+    int tail;         // valid rows of the piece's last tile, 1..32
+    bool valid;
+  };
+  auto cursor_enter = [&](Cursor& c, const Piece& pc) __attribute__((always_inline)) {
+    const int64_t len = pc.end - pc.begin;            // 1 .. segment size: fits 32 bits
+    c.user = pc.user;
+    c.row = pc.begin;
+    c.tiles_left = int((len + kTile - 1) / kTile);
+    c.tail = int(len - int64_t(c.tiles_left - 1) * kTile);
+  };
+  auto cursor_init = [&](Cursor& c) __attribute__((always_inline)) {
+    c.wuser = __builtin_amdgcn_readfirstlane(p.seg_user[g]);
+    c.wpos = seg_begin;
+    Piece pc;
+    pc.user = 0;
+    pc.begin = seg_begin;
+    pc.end = seg_begin + 1;          // overwritten unless offsets are invalid; stays inside [0, N)
+    c.valid = next_piece(p.offsets, p.B, seg_end, c.wuser, c.wpos, pc);
+    cursor_enter(c, pc);
+  };
+  auto cursor_advance = [&](Cursor& c) __attribute__((always_inline)) {
+    if (!c.valid) return;
+    if (c.tiles_left > 1) {
+      --c.tiles_left;
+      c.row += kTile;
+    } else {
+      Piece nx;
+      if (next_piece(p.offsets, p.B, seg_end, c.wuser, c.wpos, nx))
+        cursor_enter(c, nx);
+      else
+        c.valid = false;             // stays on its last tile
+    }
+  };
 
-    f32x16 o[NQB];
-    float l[NQB], m[NQB];
+  f32x16 o[NQB];
+  float l[NQB], m[NQB];
+  int mode = 0;  // 0 fresh piece, 1 constant reference 0, 2 running maximum
+  auto reset_state = [&]() __attribute__((always_inline)) {
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) {
 #pragma unroll
@@ -217,127 +275,213 @@ __device__ __forceinline__ void summarize_wave(const MfmaSummarizeParams& p, Sum
       l[qb] = 0.f;
       m[qb] = 0.f;
     }
-    int mode = 0;  // 0 fresh, 1 constant reference 0, 2 running maximum
+    mode = 0;
+  };
 
-    // HBM -> registers -> LDS movement of X; two register sets alternate so a
-    // load has two tile periods to land.
-    uint4 xra[CPT], xrb[CPT];
-    auto fetch = [&](int t, uint4 (&xr)[CPT]) {
-      if (t >= ntiles) return;
-      const int64_t r0 = pc.begin + int64_t(t) * kTile;
+  // HBM -> LDS movement of X without a stop in registers (global_load_lds, 16 bytes
+  // per lane: lane i of a wave lands at the wave's LDS base + 16 i).  Tile t lives in
+  // xbuf[t % 3]; the rows of tile t+3 are requested at the top of tile t into the
+  // buffer tile t has vacated and must have landed by the end of tile t+1, so a
+  // load has two tile periods.  Rows past the piece are clamped to its last row.
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  auto fetch = [&](const Cursor& c, int xb) __attribute__((always_inline)) {
+    const int last = (c.tiles_left == 1 ? c.tail : kTile) - 1;   // last valid row of the tile
+    const char* base = reinterpret_cast<const char*>(p.X) + c.row * (D * 2);
 #pragma unroll
-      for (int k = 0; k < CPT; ++k) {
-        const int cid = tid + k * NT;
-        int64_t row = r0 + cid / CH;
-        if (row > pc.end - 1) row = pc.end - 1;
-        xr[k] = *reinterpret_cast<const uint4*>(p.X + row * D + (cid % CH) * 8);
-      }
-    };
-    auto stash = [&](int t, int buf, const uint4 (&xr)[CPT]) {
-      if (t >= ntiles) return;
-#pragma unroll
-      for (int k = 0; k < CPT; ++k) {
-        const int cid = tid + k * NT;
-        sm.xbuf[buf][(cid % CH) * 33 + cid / CH] = xr[k];
-      }
-    };
-    // k-slices [ks0, ks1) of this wave's projection of the X tile in xbuf[buf]
-    auto project = [&](int buf, int ks0, int ks1, f32x16& acc) {
-#pragma unroll
-      for (int ks = ks0; ks < ks1; ++ks) {
-        Pack8 x;
-        x.u = sm.xbuf[buf][(2 * ks + hf) * 33 + l32];
-        acc = ROLE ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(x.v, wreg[ks], acc, 0, 0, 0)
-                   : __builtin_amdgcn_mfma_f32_32x32x16_bf16(wreg[ks], x.v, acc, 0, 0, 0);
-      }
-    };
-    // hand the projected tile to the partner wave: bf16 operand halves (+ key norms)
-    auto publish = [&](int buf, const f32x16& acc) {
-      Pack8 r0, r1;
-      float n2 = 0.f;
-#pragma unroll
-      for (int i = 0; i < 16; i += 2) {
-        const float a = ROLE ? acc[i] : acc[i] * p.c, b = ROLE ? acc[i + 1] : acc[i + 1] * p.c;
-        if (ROLE == 0) n2 = fmaf(a, a, fmaf(b, b, n2));
-        const uint32_t pk = cvt_pk_bf16(a, b);
-        if (i < 8) r0.w[i / 2] = pk; else r1.w[(i - 8) / 2] = pk;
-      }
-      sm.kvbuf[buf][hl][ROLE][0][lane] = r0.u;
-      sm.kvbuf[buf][hl][ROLE][1][lane] = r1.u;
-      if (ROLE == 0) sm.knorm[buf][hl][lane] = n2;
-    };
-    // attention over tile t (operands in kvbuf[buf]) with the projection of tile t+1 woven in
-    auto tile = [&](int t, int buf) {
-      Pack8 k0, k1, v0, v1;
-      k0.u = sm.kvbuf[buf][hl][0][0][lane];
-      k1.u = sm.kvbuf[buf][hl][0][1][lane];
-      v0.u = sm.kvbuf[buf][hl][1][0][lane];
-      v1.u = sm.kvbuf[buf][hl][1][1][lane];
-      const float kn2 = sm.knorm[buf][hl][lane] + sm.knorm[buf][hl][lane ^ 32];
-      const bool unsafe = __builtin_amdgcn_ballot_w64(kn2 * qmax2 > kSafeBound2) != 0;
-      const int64_t left = pc.end - (pc.begin + int64_t(t) * kTile);
-      const int nvalid = left < kTile ? int(left) : kTile;
-      const int nvl = nvalid - 4 * hf;
-      const bool general = unsafe || mode == 2;
-      if (general && mode == 0) {
-#pragma unroll
-        for (int qb = 0; qb < NQB; ++qb) m[qb] = -INFINITY;
-      }
-      mode = general ? 2 : 1;
-      const bool masked = nvalid < kTile;
-      const bool more = t + 1 < ntiles;
-      f32x16 acc = {0};
-#pragma unroll
-      for (int qb = 0; qb < NQB; ++qb) {
-        attend_block(k0.v, k1.v, v0.v, v1.v, qop[qb][0], qop[qb][1], o[qb], l[qb], m[qb], general, masked, nvl);
-        if (more && qb * KPB < KS) project(buf ^ 1, qb * KPB, qb * KPB + KPB, acc);
-      }
-      if (more) publish(buf ^ 1, acc);
-    };
-
-    lds_barrier();   // every wave is done with the previous piece's buffers
-    fetch(0, xra);
-    fetch(1, xrb);
-    stash(0, 0, xra);
-    fetch(2, xra);
-    lds_barrier();
-    {
-      f32x16 acc = {0};
-      project(0, 0, KS, acc);
-      publish(0, acc);
+    for (int k = 0; k < CPT; ++k) {
+      const int slot = k * NT + tid;                         // LDS slot = chunk * 32 + item
+      int rel = slot & 31;
+      if (rel > last) rel = last;
+      const uint32_t voff = uint32_t(rel) * (D * 2) + uint32_t(slot >> 5) * 16;
+      // Written as assembly so that the completion wait is the explicit vmcnt wait at
+      // the end of the next tile, not a conservative one before the next LDS read.
+      const uint32_t lds_base = uint32_t(reinterpret_cast<uintptr_t>(
+          (void __attribute__((address_space(3)))*)(&sm.xbuf[xb][k * NT + wave * 64])));
+      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+                   :
+                   : "s"(lds_base), "v"(voff), "s"(base)
+                   : "memory", "m0");
     }
-    stash(1, 1, xrb);
-    fetch(3, xrb);
-
-    for (int t = 0; t < ntiles; t += 2) {
-      lds_barrier();
-      tile(t, 0);
-      stash(t + 2, 0, xra);
-      fetch(t + 4, xra);
-      if (t + 1 < ntiles) {
-        lds_barrier();
-        tile(t + 1, 1);
-        stash(t + 3, 1, xrb);
-        fetch(t + 5, xrb);
-      }
+  };
+  // k-slices [ks0, ks1) of this wave's projection of the X tile in xbuf[buf]
+  auto project = [&](int buf, int ks0, int ks1, f32x16& acc) __attribute__((always_inline)) {
+#pragma unroll
+    for (int ks = ks0; ks < ks1; ++ks) {
+      Pack8 x, w;
+      x.u = sm.xbuf[buf][(2 * ks + hf) * 32 + l32];
+      w.u = sm.wop[hl][ROLE][ks][lane];
+      acc = ROLE ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(x.v, w.v, acc, 0, 0, 0)
+                 : __builtin_amdgcn_mfma_f32_32x32x16_bf16(w.v, x.v, acc, 0, 0, 0);
     }
+  };
+  // hand the projected tile to the partner wave: bf16 operand halves (+ key norms)
+  auto publish = [&](int buf, const f32x16& acc) __attribute__((always_inline)) {
+    Pack8 r0, r1;
+    float n2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; i += 2) {
+      const uint32_t pk = cvt_pk_bf16(acc[i], acc[i + 1]);
+      if (ROLE == 0) n2 = dot2_self(pk, n2);
+      if (i < 8) r0.w[i / 2] = pk; else r1.w[(i - 8) / 2] = pk;
+    }
+    sm.kvbuf[buf][hl][ROLE][0][lane] = r0.u;
+    sm.kvbuf[buf][hl][ROLE][1][lane] = r1.u;
+    if (ROLE == 0) sm.knorm[buf][hl][lane] = n2;
+  };
+  auto unsafe_tile = [&](int buf) __attribute__((always_inline)) {
+    const float kn2 = sm.knorm[buf][hl][lane] + sm.knorm[buf][hl][lane ^ 32];
+    return __builtin_amdgcn_ballot_w64(kn2 * qmax2 > kSafeBound2) != 0;
+  };
 
-    // ---- partial record of this piece: slot = segment + user
-    const int64_t slot = g + pc.user;
-    float* rec = p.partials + ((slot * p.H + h) * (p.S / 32) + (qbase / 32)) * kRecFloats;
+  Cursor ca, cf;
+  cursor_init(ca);
+  cf = ca;
+
+  // Common case: a full tile, bounded scores, another tile behind it.  Straight-line
+  // code (one scheduling region per tile): two projection MFMAs of the next tile ride
+  // along with every query block of this one.
+  auto fast_tile = [&](auto par_c, int xb, const Pack8& k0, const Pack8& k1, const Pack8& v0,
+                       const Pack8& v1) __attribute__((always_inline)) {   // par_c = parity of the tile index
+    constexpr int buf = decltype(par_c)::value;                                // xb = tile index mod 3
+    const int xb_next = xb == kXBuf - 1 ? 0 : xb + 1;
+    f32x16 acc = {0};
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) {
-      float* r = rec + qb * kRecFloats + lane;
+      f32x16 sc = {0};
+      sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0.v, qop[qb][0], sc, 0, 0, 0);
+      sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1.v, qop[qb][1], sc, 0, 0, 0);
+      if (qb * KPB < KS) project(xb_next, qb * KPB, qb * KPB + KPB, acc);
+      Pack8 p0, p1;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) r[i * 64] = o[qb][i];
-      r[16 * 64] = l[qb] + __shfl_xor(l[qb], 32, 64);
-      r[17 * 64] = m[qb];
+      for (int i = 0; i < 16; i += 2) {
+        const uint32_t pk = cvt_pk_bf16(__builtin_amdgcn_exp2f(sc[i]), __builtin_amdgcn_exp2f(sc[i + 1]));
+        l[qb] = dot2_ones(pk, l[qb]);
+        if (i < 8) p0.w[i / 2] = pk; else p1.w[(i - 8) / 2] = pk;
+      }
+      o[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v0.v, p0.v, o[qb], 0, 0, 0);
+      o[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v1.v, p1.v, o[qb], 0, 0, 0);
     }
+    publish(buf ^ 1, acc);
+  };
+
+  // Any tile: ragged tail, scores beyond the bound, last tile of the segment.
+  auto slow_tile = [&](auto par_c, int xb, int nvalid, bool more, bool unsafe, const Pack8& k0,
+                       const Pack8& k1, const Pack8& v0, const Pack8& v1) __attribute__((always_inline)) {
+    constexpr int buf = decltype(par_c)::value;
+    const int xb_next = xb == kXBuf - 1 ? 0 : xb + 1;
+    const int nvl = nvalid - 4 * hf;
+    const bool general = mode == 2 || unsafe;
+    if (mode != 2) {   // the reference so far: nothing (fresh piece) or the constant 0
+#pragma unroll
+      for (int qb = 0; qb < NQB; ++qb) m[qb] = (general && mode == 0) ? -INFINITY : 0.f;
+    }
+    mode = general ? 2 : 1;
+    const bool masked = nvalid < kTile;
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb)
+      attend_block(k0.v, k1.v, v0.v, v1.v, qop[qb][0], qop[qb][1], o[qb], l[qb], m[qb], general, masked, nvl);
+    if (more) {
+      f32x16 acc = {0};
+      project(xb_next, 0, KS, acc);
+      publish(buf ^ 1, acc);
+    }
+  };
+
+  // partial record of a finished piece: slot = segment + user
+  auto write_partial = [&](int user) __attribute__((always_inline)) {
+    const int64_t slot = g + user;
+    char* rec = reinterpret_cast<char*>(p.partials +
+                                        ((slot * p.H + h) * (p.S / 32) + (qbase / 32)) * kRecFloats);
+    const uint32_t lane_off = uint32_t(lane) * 4;
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) {
+      char* r = rec + size_t(qb) * kRecFloats * 4;       // scalar
+#pragma unroll
+      for (int i = 0; i < 16; ++i) *reinterpret_cast<float*>(r + i * 256 + lane_off) = o[qb][i];
+      *reinterpret_cast<float*>(r + 16 * 256 + lane_off) = l[qb] + __shfl_xor(l[qb], 32, 64);
+      *reinterpret_cast<float*>(r + 17 * 256 + lane_off) = (mode == 2) ? m[qb] : 0.f;
+    }
+  };
+
+  if (!ca.valid) return;               // only with invalid offsets (whole workgroup)
+  reset_state();
+  if (p.q_user_stride != 0) load_queries(ca.user);
+
+  // Waits until at most `pending` of this wave's newest vector-memory operations
+  // are outstanding (s_waitcnt vmcnt only; the other counters are left alone).
+  auto wait_vm = [&](auto n_c) __attribute__((always_inline)) {
+    constexpr int n = decltype(n_c)::value;
+    __builtin_amdgcn_s_waitcnt((n & 0xF) | ((n >> 4) << 14) | 0x0F70);
+  };
+
+  // ---- prologue: tiles 0, 1, 2 requested; tiles 0 and 1 landed; tile 0 projected
+  fetch(cf, 0);
+  cursor_advance(cf);
+  fetch(cf, 1);
+  cursor_advance(cf);
+  fetch(cf, 2);
+  cursor_advance(cf);
+  wait_vm(Int<CPT>{});
+  lds_barrier();
+  {
+    f32x16 acc = {0};
+    project(0, 0, KS, acc);
+    publish(0, acc);
+  }
+
+  // One trip = one tile; exactly one barrier per tile on either route (waves may
+  // take different routes: the bound depends on each wave's queries).
+  int parity = 0, xb = 0;
+  bool drain = true;      // other vector-memory traffic (record stores, query loads) is in flight
+  // One tile: request tile t+3, read this tile's K/V operands and key norms in one
+  // burst (LDS answers in order, so the norm test costs no extra round trip), then
+  // take the straight-line route or the general one.
+  auto one_tile = [&](auto par_c) __attribute__((always_inline)) {
+    constexpr int buf = decltype(par_c)::value;
+    fetch(cf, xb);
+    Pack8 k0, k1, v0, v1;
+    k0.u = sm.kvbuf[buf][hl][0][0][lane];
+    k1.u = sm.kvbuf[buf][hl][0][1][lane];
+    v0.u = sm.kvbuf[buf][hl][1][0][lane];
+    v1.u = sm.kvbuf[buf][hl][1][1][lane];
+    const bool unsafe = unsafe_tile(buf);
+    const bool last_in_piece = ca.tiles_left == 1;
+    const int nvalid = last_in_piece ? ca.tail : kTile;
+    const bool more = !(last_in_piece && ca.wpos >= seg_end);
+    if (nvalid == kTile && more && mode != 2 && !unsafe) {
+      mode = 1;
+      fast_tile(par_c, xb, k0, k1, v0, v1);
+    } else {
+      slow_tile(par_c, xb, nvalid, more, unsafe, k0, k1, v0, v1);
+    }
+  };
+
+  while (ca.valid) {
+    lds_barrier();
+    const bool last_in_piece = ca.tiles_left == 1;
+    if (parity == 0) one_tile(Int<0>{}); else one_tile(Int<1>{});
+    // Tile t+2 (requested one tile ago) must have landed before the next barrier;
+    // the request just issued for tile t+3 may stay in flight.  Loads complete in
+    // order among themselves but not with respect to stores, so after a record
+    // write everything is drained once.
+    if (drain) wait_vm(Int<0>{}); else wait_vm(Int<CPT>{});
+    drain = false;
+    cursor_advance(cf);
+    const int done_user = ca.user;
+    cursor_advance(ca);
+    if (last_in_piece) {
+      write_partial(done_user);
+      reset_state();
+      if (p.q_user_stride != 0 && ca.valid) load_queries(ca.user);
+      drain = true;
+    }
+    parity ^= 1;
+    xb = xb == kXBuf - 1 ? 0 : xb + 1;
   }
 }
 
 template <int D, int NQB, int HPW>
-__global__ __launch_bounds__(HPW * 128, (HPW == 1 ? 2 : 1)) void summarize_mfma_kernel(MfmaSummarizeParams p) {
+__global__ __launch_bounds__(HPW * 128) void summarize_mfma_kernel(MfmaSummarizeParams p) {
   __shared__ SummarizeLds<D, HPW> sm;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform, kept scalar
   const int hl = wave >> 1;
@@ -361,8 +505,8 @@ __global__ __launch_bounds__(HPW * 128, (HPW == 1 ? 2 : 1)) void summarize_mfma_
 }
 
 // Merge of a user's partial records, ascending segment order (fixed, so the
-// result is bitwise reproducible):  m = max m_c, w_c = 2^(m_c - m),
-// out = sum_c w_c O_c / sum_c w_c l_c.   grid (S/32, H, B), 256 threads: wave w
+// result is bitwise reproducible): with m the running maximum of the m_c,
+// out = sum_c 2^(m_c - m) O_c / sum_c 2^(m_c - m) l_c.   grid (S/32, H, B), 256 threads: wave w
 // owns accumulator registers 4w..4w+3, i.e. channels 8w + 4 hf + 0..3.
 __global__ __launch_bounds__(256) void merge_mfma_kernel(const float* __restrict__ partials,
                                                          const int64_t* __restrict__ offsets, int S, int d,
@@ -381,18 +525,36 @@ __global__ __launch_bounds__(256) void merge_mfma_kernel(const float* __restrict
   if (g0 < 0) g0 = 0;
   if (g1 > G - 1) g1 = G - 1;
   const int nqb = S / 32;
-  auto rec = [&](int64_t g) { return partials + (((g + b) * H + h) * nqb + qb) * kRecFloats + lane; };
-  float m = -INFINITY;
-  for (int64_t g = g0; g <= g1; ++g) m = fmaxf(m, rec(g)[17 * 64]);
-  float l = 0.f, o0 = 0.f, o1 = 0.f, o2 = 0.f, o3 = 0.f;
-  for (int64_t g = g0; g <= g1; ++g) {
-    const float* r = rec(g);
-    const float wgt = exp2f(r[17 * 64] - m);
-    l = fmaf(r[16 * 64], wgt, l);
-    o0 = fmaf(r[(4 * w + 0) * 64], wgt, o0);
-    o1 = fmaf(r[(4 * w + 1) * 64], wgt, o1);
-    o2 = fmaf(r[(4 * w + 2) * 64], wgt, o2);
-    o3 = fmaf(r[(4 * w + 3) * 64], wgt, o3);
+  auto rec = [&](int64_t g) __attribute__((always_inline)) { return partials + (((g + b) * H + h) * nqb + qb) * kRecFloats + lane; };
+  // One pass with a running maximum (rescale when it moves); loads are issued kBatch
+  // records at a time so a long user is not a chain of dependent round trips.
+  constexpr int kBatch = 8;
+  float m = -INFINITY, l = 0.f, o0 = 0.f, o1 = 0.f, o2 = 0.f, o3 = 0.f;
+  for (int64_t g = g0; g <= g1; g += kBatch) {
+    float v[kBatch][6];
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const bool on = g + u <= g1;
+      const float* r = rec(on ? g + u : g1);
+      v[u][0] = on ? r[17 * 64] : -INFINITY;
+      v[u][1] = r[16 * 64];
+      v[u][2] = r[(4 * w + 0) * 64];
+      v[u][3] = r[(4 * w + 1) * 64];
+      v[u][4] = r[(4 * w + 2) * 64];
+      v[u][5] = r[(4 * w + 3) * 64];
+    }
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {     // ascending segment order
+      const float mn = fmaxf(m, v[u][0]);
+      const float keep = exp2f(m - mn);       // 0 on the first record (m = -inf), 1 while the maximum stands
+      const float wgt = exp2f(v[u][0] - mn);  // 0 for the padding entries
+      l = fmaf(v[u][1], wgt, l * keep);
+      o0 = fmaf(v[u][2], wgt, o0 * keep);
+      o1 = fmaf(v[u][3], wgt, o1 * keep);
+      o2 = fmaf(v[u][4], wgt, o2 * keep);
+      o3 = fmaf(v[u][5], wgt, o3 * keep);
+      m = mn;
+    }
   }
   const float inv = 1.f / l;
   uint2 pk;
@@ -418,7 +580,8 @@ static size_t partial_bytes(const vista_summarize_desc& d, int seg) {
 }
 
 size_t mfma_summarize_workspace(const vista_summarize_desc& d, int seg) {
-  return kHeaderBytes + ((partial_bytes(d, seg) + 255) & ~size_t(255));
+  const int64_t G = (d.total_items + seg - 1) / seg;
+  return kHeaderBytes + plan_bytes(G) + ((partial_bytes(d, seg) + 255) & ~size_t(255));
 }
 
 template <int D, int NQB, int HPW>
@@ -437,7 +600,9 @@ vista_status mfma_summarize(const SummarizeArgs& a) {
   p.q_user_stride = d.q_user_stride;
   p.Wk = static_cast<const uint16_t*>(a.Wk);
   p.Wv = static_cast<const uint16_t*>(a.Wv);
-  p.partials = reinterpret_cast<float*>(a.workspace + kHeaderBytes);
+  p.partials = reinterpret_cast<float*>(a.workspace + kHeaderBytes + plan_bytes(a.G));
+  p.seg_user = a.seg_user;
+
   p.B = d.B;
   p.S = d.S;
   p.H = d.H;
@@ -452,12 +617,7 @@ vista_status mfma_summarize(const SummarizeArgs& a) {
         case 64: launch_main<128, 1, 4>(p, a.G, a.stream); break;
         case 128: launch_main<128, 2, 4>(p, a.G, a.stream); break;
         case 256:
-#ifdef EXP_HPW1
-          p.nhg = 4;
-          launch_main<128, 4, 1>(p, a.G, a.stream);
-#else
           launch_main<128, 4, 4>(p, a.G, a.stream);
-#endif
           break;
         default:
           p.nhg = 2;

@@ -99,7 +99,9 @@ vista_status vista_summarize(const vista_summarize_desc* desc, const void* histo
   a.workspace = static_cast<char*>(workspace);
   a.stream = static_cast<hipStream_t>(hip_stream);
 
-  launch_check_offsets(offsets, desc->B, desc->total_items, reinterpret_cast<int*>(workspace), a.stream);
+  int* seg_user = reinterpret_cast<int*>(a.workspace + kHeaderBytes);
+  a.seg_user = seg_user;
+  launch_plan(offsets, desc->B, desc->total_items, a.seg, a.G, reinterpret_cast<int*>(workspace), seg_user, a.stream);
   if (hipGetLastError() != hipSuccess) return VISTA_ERR_HIP;
   return mfma_summarize_supported(*desc) ? mfma_summarize(a) : generic_summarize(a);
 }
