@@ -33,6 +33,13 @@ from paper_2510_22049_amd import inputs as I
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
+# HBM bytes per launch of the dominant kernels on exactly these workloads, from two
+# `rocprofv3 --pmc` runs of this script (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch), each
+# scaled by what the same counter reads for the 1 GiB copy of --calibrate-copy (FETCH_SIZE
+# reads half the bytes on this part: factor 2.0; WRITE_SIZE factor 1.0).
+TRAFFIC_STAGE1_BYTES = (97404.0 * 2.0 + 46704.0) * 1024    # summarize_mfma_kernel: X read once + partial records written
+TRAFFIC_STAGE2_BYTES = (98384.2 * 2.0 + 131072.0) * 1024   # attend_mfma_kernel: candidates + summaries read, outputs written
+
 
 def bf16_dev(x: np.ndarray) -> torch.Tensor:
     return torch.from_numpy(x).cuda().to(torch.bfloat16)
@@ -94,18 +101,19 @@ def cpu_baseline(host, c, budget_s: float = 12.0):
     except Exception:
         cores = os.cpu_count() or 1
     order = np.argsort(host["lens"])            # shortest users first so the sample is bounded
-    items, t0, used = 0, time.perf_counter(), []
-    for b in order:
-        lo, hi = host["off"][b], host["off"][b + 1]
-        O.summarize(host["X"][lo:hi], [0, hi - lo], host["Q"], host["Wk"], host["Wv"], c.H)
-        items += int(hi - lo)
-        used.append(int(b))
-        if time.perf_counter() - t0 > budget_s:
-            break
+    items, users, t0 = 0, 0, time.perf_counter()
+    while time.perf_counter() - t0 < budget_s:  # whole passes over the users until the budget is spent
+        for b in order:
+            lo, hi = host["off"][b], host["off"][b + 1]
+            O.summarize(host["X"][lo:hi], [0, hi - lo], host["Q"], host["Wk"], host["Wv"], c.H)
+            items += int(hi - lo)
+            users += 1
+            if time.perf_counter() - t0 > budget_s:
+                break
     dt = time.perf_counter() - t0
     return {"value": items / dt, "unit": "items/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"stage 1, {len(used)} shortest of 64 users of the jagged-batch workload, "
-                      f"{items} items in {dt:.1f} s (fp64 numpy)"}
+            "sample": f"stage 1, {users} user histories of the jagged-batch workload (passes over the 64 users, "
+                      f"shortest first), {items} items in {dt:.1f} s (fp64 numpy oracle)"}
 
 
 def main() -> None:
@@ -115,6 +123,8 @@ def main() -> None:
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--segment-items", type=int, default=0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 1 GiB device copy (a kernel of known traffic for scaling HBM counters)")
     a = ap.parse_args()
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -123,6 +133,12 @@ def main() -> None:
     V.lib()
     torch.cuda.set_device(0)
     SETS = 4
+    if a.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")      # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ------------------------------------------------------------- stage 1
     c1, N, dev, xs, outs, ws, host = stage1_workload(SETS)
@@ -163,13 +179,16 @@ def main() -> None:
                    "segment_items": V.vista_summarize_segment_items(
                        V.summarize_desc(c1.B, c1.S, c1.d, c1.H, V.VISTA_BF16, N, segment_items=a.segment_items))},
         "roofline": {"bound": "mfma", "achieved": tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": tflops / PEAK_BF16_TFLOPS, "traffic": None,
+                     "frac": tflops / PEAK_BF16_TFLOPS, "traffic": TRAFFIC_STAGE1_BYTES,
                      "kernel": "summarize_mfma_kernel<128,4,4>", "flop_per_item": flop_item,
-                     "note": "duration = whole vista_summarize call (offset check + main + merge kernels)"},
+                     "algorithmic_bytes": N * c1.d * 2,
+                     "note": "duration = one whole vista_summarize call (plan + summarize_mfma + merge kernels, "
+                             "HIP events on the launch stream); the kernel-only average is in profiles/"},
         "stage2": {"value": cand_per_s, "unit": "candidate scores/s", "ms_per_step": ms2,
                    "config": {"workload": "stage-2 serving: 1024 users x 512 candidates, S=256, d=128, 4 heads, bf16"},
                    "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                                "frac": gbs / PEAK_HBM_GBS, "traffic": None, "bytes_per_candidate": bytes_cand}},
+                                "frac": gbs / PEAK_HBM_GBS, "traffic": TRAFFIC_STAGE2_BYTES,
+                                "kernel": "attend_mfma_kernel<8>", "bytes_per_candidate": bytes_cand}},
     }
     if not a.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(host, c1)

@@ -2,16 +2,19 @@
 //
 // One workgroup streams one flat segment of the packed history for HPW heads.
 // Each head is served by a pair of waves.  Per tile of 32 items:
-//   1. the workgroup copies the X tile (32 x D bf16) from HBM into LDS once;
-//   2. wave "K" of a pair forms K_h^T = (scale*log2e W_k,h)^T X^T,
-//      wave "V" forms V_h = X W_v,h -- eight 32x32x16 MFMAs each for D = 128 --
-//      and both hand the bf16 result to their partner through LDS;
+//   1. the X tile (32 x D bf16) goes from HBM straight into LDS (direct
+//      global->LDS loads, three tiles deep, no stop in registers);
+//   2. wave "K" of a pair forms K_h^T = (scale*log2e W_k,h)^T X^T, wave "V" forms
+//      V_h = X W_v,h -- eight 32x32x16 MFMAs each for D = 128, weights read as
+//      LDS operands -- and both hand the bf16 result to their partner through LDS;
 //   3. each wave owns half of the S queries: for every block of 32 queries
 //      S^T = K_h Q_h^T (items x queries), p = 2^(s - m), O^T += V_h^T P^T.
 // With items on the MFMA row index and queries on the column index, every lane
 // owns one query column: the softmax statistics are per-lane scalars, the
 // fp32 score registers turn into the bf16 P operand without any shuffle, and
 // the projected K^T / V accumulators already are the next MFMA's A operand.
+// The projection of tile t+1 rides along with the attention over tile t, and
+// the tiles of all pieces (user x segment) of the segment form one stream.
 //
 // Softmax reference.  Scores are kept in base-2 units.  While every score of a
 // tile is provably inside [-60, 60] (Cauchy-Schwarz: |q| |k| <= 60) the
@@ -20,8 +23,8 @@
 // there.  A tile that fails the test switches the piece to the usual running
 // maximum with rescaling.  Both routes evaluate the same softmax exactly.
 //
-// Each piece (segment x user) ends with one partial record (O, l, m) per head;
-// merge_mfma_kernel combines a user's records in ascending segment order.
+// Each piece ends with one partial record (O, l, m) per head; merge_mfma_kernel
+// combines a user's records in ascending segment order.
 #include "common.hpp"
 
 namespace vista {
