@@ -343,9 +343,8 @@ __device__ __forceinline__ void summarize_wave(const MfmaSummarizeParams& p, Sum
   // Common case: a full tile, bounded scores, another tile behind it.  Straight-line
   // code (one scheduling region per tile): two projection MFMAs of the next tile ride
   // along with every query block of this one.
-  auto fast_tile = [&](auto par_c, int xb, const Pack8& k0, const Pack8& k1, const Pack8& v0,
-                       const Pack8& v1) __attribute__((always_inline)) {   // par_c = parity of the tile index
-    constexpr int buf = decltype(par_c)::value;                                // xb = tile index mod 3
+  auto fast_tile = [&](int buf, int xb, const Pack8& k0, const Pack8& k1, const Pack8& v0,
+                       const Pack8& v1) __attribute__((always_inline)) {   // buf = tile index mod 2, xb = mod 3
     const int xb_next = xb == kXBuf - 1 ? 0 : xb + 1;
     f32x16 acc = {0};
 #pragma unroll
@@ -363,14 +362,16 @@ __device__ __forceinline__ void summarize_wave(const MfmaSummarizeParams& p, Sum
       }
       o[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v0.v, p0.v, o[qb], 0, 0, 0);
       o[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v1.v, p1.v, o[qb], 0, 0, 0);
+#ifdef EXP_SB
+      __builtin_amdgcn_sched_barrier(0);
+#endif
     }
     publish(buf ^ 1, acc);
   };
 
   // Any tile: ragged tail, scores beyond the bound, last tile of the segment.
-  auto slow_tile = [&](auto par_c, int xb, int nvalid, bool more, bool unsafe, const Pack8& k0,
+  auto slow_tile = [&](int buf, int xb, int nvalid, bool more, bool unsafe, const Pack8& k0,
                        const Pack8& k1, const Pack8& v0, const Pack8& v1) __attribute__((always_inline)) {
-    constexpr int buf = decltype(par_c)::value;
     const int xb_next = xb == kXBuf - 1 ? 0 : xb + 1;
     const int nvl = nvalid - 4 * hf;
     const bool general = mode == 2 || unsafe;
@@ -432,44 +433,54 @@ __device__ __forceinline__ void summarize_wave(const MfmaSummarizeParams& p, Sum
     publish(0, acc);
   }
 
-  // One trip = one tile; exactly one barrier per tile on either route (waves may
-  // take different routes: the bound depends on each wave's queries).
+  // One barrier per tile on either route (waves may take different routes: the bound
+  // depends on each wave's queries).  Runs of plain tiles (full, bounded scores, not
+  // the last of their piece) stay in the inner loop, whose body is straight-line
+  // code with the accumulators updated in place; every other tile leaves it, takes
+  // the general route and does the piece bookkeeping.
   int parity = 0, xb = 0;
   bool drain = true;      // other vector-memory traffic (record stores, query loads) is in flight
-  // One tile: request tile t+3, read this tile's K/V operands and key norms in one
-  // burst (LDS answers in order, so the norm test costs no extra round trip), then
-  // take the straight-line route or the general one.
-  auto one_tile = [&](auto par_c) __attribute__((always_inline)) {
-    constexpr int buf = decltype(par_c)::value;
-    fetch(cf, xb);
-    Pack8 k0, k1, v0, v1;
-    k0.u = sm.kvbuf[buf][hl][0][0][lane];
-    k1.u = sm.kvbuf[buf][hl][0][1][lane];
-    v0.u = sm.kvbuf[buf][hl][1][0][lane];
-    v1.u = sm.kvbuf[buf][hl][1][1][lane];
-    const bool unsafe = unsafe_tile(buf);
-    const bool last_in_piece = ca.tiles_left == 1;
-    const int nvalid = last_in_piece ? ca.tail : kTile;
-    const bool more = !(last_in_piece && ca.wpos >= seg_end);
-    if (nvalid == kTile && more && mode != 2 && !unsafe) {
-      mode = 1;
-      fast_tile(par_c, xb, k0, k1, v0, v1);
-    } else {
-      slow_tile(par_c, xb, nvalid, more, unsafe, k0, k1, v0, v1);
-    }
-  };
-
-  while (ca.valid) {
-    lds_barrier();
-    const bool last_in_piece = ca.tiles_left == 1;
-    if (parity == 0) one_tile(Int<0>{}); else one_tile(Int<1>{});
-    // Tile t+2 (requested one tile ago) must have landed before the next barrier;
-    // the request just issued for tile t+3 may stay in flight.  Loads complete in
-    // order among themselves but not with respect to stores, so after a record
-    // write everything is drained once.
+  // Tile t+2 (requested one tile ago) must have landed before the next barrier; the
+  // request just issued for tile t+3 may stay in flight.  Loads complete in order
+  // among themselves but not with respect to stores, so after a record write
+  // everything is drained once.
+  auto end_of_tile = [&]() __attribute__((always_inline)) {
     if (drain) wait_vm(Int<0>{}); else wait_vm(Int<CPT>{});
     drain = false;
     cursor_advance(cf);
+  };
+  Pack8 k0, k1, v0, v1;
+  bool unsafe;
+  // Start of a tile: request tile t+3, read this tile's K/V operands and key norms in
+  // one burst (LDS answers in order, so the norm test costs no extra round trip).
+  // Returns whether the tile is a plain one.
+  auto begin_tile = [&]() __attribute__((always_inline)) {
+    lds_barrier();
+    fetch(cf, xb);
+    k0.u = sm.kvbuf[parity][hl][0][0][lane];
+    k1.u = sm.kvbuf[parity][hl][0][1][lane];
+    v0.u = sm.kvbuf[parity][hl][1][0][lane];
+    v1.u = sm.kvbuf[parity][hl][1][1][lane];
+    unsafe = unsafe_tile(parity);
+    return !(ca.tiles_left == 1 || mode == 2 || unsafe);
+  };
+  bool plain = begin_tile();
+  for (;;) {
+    while (__builtin_expect(plain, 1)) {
+      mode = 1;
+      fast_tile(parity, xb, k0, k1, v0, v1);
+      end_of_tile();
+      --ca.tiles_left;
+      ca.row += kTile;
+      parity ^= 1;
+      xb = xb == kXBuf - 1 ? 0 : xb + 1;
+      plain = begin_tile();
+    }
+    const bool last_in_piece = ca.tiles_left == 1;
+    const int nvalid = last_in_piece ? ca.tail : kTile;
+    const bool more = !(last_in_piece && ca.wpos >= seg_end);
+    slow_tile(parity, xb, nvalid, more, unsafe, k0, k1, v0, v1);
+    end_of_tile();
     const int done_user = ca.user;
     cursor_advance(ca);
     if (last_in_piece) {
@@ -480,6 +491,8 @@ __device__ __forceinline__ void summarize_wave(const MfmaSummarizeParams& p, Sum
     }
     parity ^= 1;
     xb = xb == kXBuf - 1 ? 0 : xb + 1;
+    if (!ca.valid) break;
+    plain = begin_tile();
   }
 }
 
