@@ -347,24 +347,31 @@ __device__ __forceinline__ void summarize_wave(const MfmaSummarizeParams& p, Sum
                        const Pack8& v1) __attribute__((always_inline)) {   // buf = tile index mod 2, xb = mod 3
     const int xb_next = xb == kXBuf - 1 ? 0 : xb + 1;
     f32x16 acc = {0};
+    // scores run one query block ahead of the exponentials that consume them
+    f32x16 nx = {0};
+    nx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0.v, qop[0][0], nx, 0, 0, 0);
+    nx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1.v, qop[0][1], nx, 0, 0, 0);
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) {
-      f32x16 sc = {0};
-      sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0.v, qop[qb][0], sc, 0, 0, 0);
-      sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1.v, qop[qb][1], sc, 0, 0, 0);
+      const f32x16 sc = nx;
+      if (qb + 1 < NQB) {
+        const f32x16 z = {0};
+        nx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0.v, qop[qb + 1][0], z, 0, 0, 0);
+        nx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1.v, qop[qb + 1][1], nx, 0, 0, 0);
+      }
       if (qb * KPB < KS) project(xb_next, qb * KPB, qb * KPB + KPB, acc);
+      // The denominator adds the weights before their rounding to bf16 (plain adds run
+      // beside the matrix core; the packed dot product does not).
       Pack8 p0, p1;
 #pragma unroll
       for (int i = 0; i < 16; i += 2) {
-        const uint32_t pk = cvt_pk_bf16(__builtin_amdgcn_exp2f(sc[i]), __builtin_amdgcn_exp2f(sc[i + 1]));
-        l[qb] = dot2_ones(pk, l[qb]);
+        const float ea = __builtin_amdgcn_exp2f(sc[i]), eb = __builtin_amdgcn_exp2f(sc[i + 1]);
+        const uint32_t pk = cvt_pk_bf16(ea, eb);
+        l[qb] += ea + eb;
         if (i < 8) p0.w[i / 2] = pk; else p1.w[(i - 8) / 2] = pk;
       }
       o[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v0.v, p0.v, o[qb], 0, 0, 0);
       o[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v1.v, p1.v, o[qb], 0, 0, 0);
-#ifdef EXP_SB
-      __builtin_amdgcn_sched_barrier(0);
-#endif
     }
     publish(buf ^ 1, acc);
   };
