@@ -1,8 +1,9 @@
 // Stage 2 on the matrix cores (bf16 MFMA, fp32 accumulate), gfx950.
 //
-// One workgroup (8 waves) serves one user and four heads; a round scores 64
+// One workgroup (4 waves) serves one user and two heads; a round scores 64
 // candidates: wave (head h, half c) takes the 32 candidates of half c for
-// head h.  The user's S summary tokens of a head are resident twice: as the K
+// head h.  Several workgroups share a compute unit (three at S = 256), so one
+// group's operand set-up hides behind the others' rounds.  The user's S summary tokens of a head are resident twice: as the K
 // operand of S^T = K Q^T (keys x candidates) in each wave's registers, and,
 // transposed, as the V operand of O^T = V^T P^T in LDS, shared by the head's two
 // waves.  The transposed copy is made by the matrix core itself (K block times
@@ -10,12 +11,15 @@
 // layout of the second product).
 //
 // HBM traffic is fully coalesced and never touches vector registers on the way
-// in: the 64 x 256 B candidate tile of the next round is brought in by direct
-// global->LDS loads (each 16 lanes fetch one whole row) while this round is
-// computed; the finished 64 x 256 B output tile is staged in LDS and stored as
-// whole rows one round later.  Both tiles keep their 16-byte chunks at position
-// chunk XOR (row mod 16), so row-wise fills and column-wise operand accesses are
-// both free of bank conflicts.
+// in.  The user's S x 128 B slab of summaries is brought in by one burst of
+// direct global->LDS loads (each 8 lanes fetch the two heads' 128 bytes of a row) into the region
+// that will hold the V operands; every wave lifts its K operands out of it, and
+// after a barrier the region is overwritten with the V operands.  Candidates
+// arrive the same way, but each wave fetches only its own 32 rows x 64 B of the
+// next round while it computes this one, writes its results over them, and
+// stores them one round later, so the round loop needs no barrier at all.  Slab
+// and parts keep their 16-byte chunks at a position XOR-ed with row bits, so
+// row-wise fills and column-wise operand accesses are free of bank conflicts.
 //
 // Key blocks stream past a candidate block (scores -> 2^s -> P V accumulate);
 // a lane owns one candidate column, so the softmax statistics are per-lane.
@@ -35,7 +39,6 @@ namespace {
 
 constexpr float kSafeBound2 = 3600.f;
 constexpr int kRound = 64;                 // candidates per round
-constexpr int kTileChunks = kRound * 16;   // 16-byte chunks of a 64 x 256 B tile
 
 struct AttendParams {
   const uint16_t* cand;
@@ -74,144 +77,208 @@ __device__ __forceinline__ void lds_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-template <int NKB>
+constexpr int kHeads = 2;                  // heads per workgroup
+constexpr int kWaves = 2 * kHeads;         // waves per workgroup
+constexpr int kThreads = 64 * kWaves;
+constexpr int kRowChunks = 4 * kHeads;     // 16-byte chunks of a workgroup's slice of a row
+// Buffers per wave (a deeper queue of parts buys nothing: a round outlasts the memory latency).
+constexpr int part_buffers(int) { return 2; }
+
+template <int NKB, int NB>
 struct AttendLds {
-  uint4 qbuf[2][kTileChunks];        // candidate tiles: row r, chunk c at [r * 16 + (c ^ (r & 15))]
-  uint4 obuf[2][kTileChunks];        // output tiles, same arrangement
-  uint4 vop[4][NKB][2][64];          // V operands: [head][key block][half of the 16 registers][lane]
+  uint4 part[kWaves][NB][128];            // per wave, NB buffers: its 32 candidates x 64 B of a round, overwritten by
+                                     // their outputs; row r, chunk c at [r * 4 + (c ^ ((r >> 2) & 3))]
+  union {
+    uint4 vop[NKB][kHeads][2][64];   // V operands: [key block][head][half of the 16 registers][lane]
+    uint4 slab[NKB * 32 * kRowChunks];   // before that: the raw summaries: row r, chunk c at [r * 8 + (c ^ ((r >> 1) & 7))]
+  };
 };
+
+template <int V>
+struct Int { static constexpr int value = V; };
 
 // NKB = S / 32 key blocks.
 template <int NKB>
-__global__ __launch_bounds__(512) void attend_mfma_kernel(AttendParams p) {
-  __shared__ AttendLds<NKB> sm;
+__global__ __launch_bounds__(kThreads, (NKB <= 6 || NKB == 8) ? 3 : 2) void attend_mfma_kernel(AttendParams p) {
+  constexpr int NB = part_buffers(NKB);
+  __shared__ AttendLds<NKB, NB> sm;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int hl = wave >> 1;            // head within the group of four
+  const int hl = wave >> 1;            // head within the group of two
   const int half = wave & 1;           // which 32 candidates of a round
   const int hf = lane >> 5, l32 = lane & 31;
-  const int hgroups = p.H / 4;
+  const int hgroups = p.H / kHeads;
   int id = blockIdx.x;
   const int chunk = id % p.chunks;
   id /= p.chunks;
   const int hg = id % hgroups;
   const int b = id / hgroups;
-  const int h = hg * 4 + hl;
   const int row_bytes = p.d * 2;
-  const int slice = hg * 256;          // byte offset of this head group's 128 channels inside a row
+  const int slice = hg * (64 * kHeads);   // byte offset of this head group's channels inside a row
 
   const int nrounds_total = (p.C + kRound - 1) / kRound;
   const int r0 = chunk * p.rounds_per_wg;
   int r1 = r0 + p.rounds_per_wg;
   if (r1 > nrounds_total) r1 = nrounds_total;
+  if (r0 >= r1) return;                // whole workgroup
   const char* Tb = reinterpret_cast<const char*>(p.cand) + int64_t(b) * p.C * row_bytes + slice;
   char* Ob = reinterpret_cast<char*>(p.out) + int64_t(b) * p.C * row_bytes + slice;
+  const char* Yb = reinterpret_cast<const char*>(p.summ) + int64_t(b) * p.S * row_bytes + slice;
 
-  // Direct global->LDS fill of one candidate tile: two 16-byte loads per lane; lane l of
-  // instruction i of wave w fills LDS chunk j = (2 w + i) * 64 + l, i.e. tile row j / 16,
-  // and fetches that row's chunk (j % 16) ^ (row % 16).  Rows past C are clamped.
-  auto fill = [&](int round, int qb) __attribute__((always_inline)) {
+  // Direct global->LDS load of 64 x 16 bytes: lane l lands at dst + 16 l.
+  auto dma = [&](const uint4* dst, const char* base, uint32_t voff) __attribute__((always_inline)) {
+    const uint32_t lds_base =
+        uint32_t(reinterpret_cast<uintptr_t>((void __attribute__((address_space(3)))*)(dst)));
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_base), "v"(voff), "s"(base)
+                 : "memory", "m0");
+  };
+  // Waits until at most n of this wave's newest vector-memory operations are outstanding.
+  auto wait_vm = [&](auto n_c) __attribute__((always_inline)) {
+    constexpr int n = decltype(n_c)::value;
+    __builtin_amdgcn_s_waitcnt((n & 0xF) | ((n >> 4) << 14) | 0x0F70);
+  };
+  // A wave moves its own part of a round and nobody else touches it, so the round loop
+  // needs no barrier.  Fill: two loads per lane; lane l of instruction i fills chunk
+  // q = 64 i + l of the part, i.e. row q / 4, and fetches that row's chunk
+  // (q % 4) ^ ((row >> 2) % 4) of the head's 64 bytes.  Rows past C are clamped.
+  auto fill = [&](int round, int tb) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-      const int j = (2 * wave + i) * 64 + lane;
-      const int row = j >> 4;
-      int cand = round * kRound + row;
+      const int q = i * 64 + lane;
+      const int row = q >> 2;
+      int cand = round * kRound + 32 * half + row;
       if (cand > p.C - 1) cand = p.C - 1;
-      const uint32_t voff = uint32_t(cand) * uint32_t(row_bytes) + uint32_t(((j & 15) ^ (row & 15)) * 16);
-      const uint32_t lds_base = uint32_t(reinterpret_cast<uintptr_t>(
-          (void __attribute__((address_space(3)))*)(&sm.qbuf[qb][(2 * wave + i) * 64])));
-      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
-                   :
-                   : "s"(lds_base), "v"(voff), "s"(Tb)
-                   : "memory", "m0");
+      dma(&sm.part[wave][tb][i * 64], Tb,
+          uint32_t(cand) * uint32_t(row_bytes) + uint32_t(64 * hl + ((q & 3) ^ ((row >> 2) & 3)) * 16));
     }
   };
-  // Whole-row store of a finished output tile (rows past C are skipped).
-  auto drain = [&](int round, int ob) __attribute__((always_inline)) {
+  // Store of a finished part, 64 contiguous bytes per row (rows past C are skipped).
+  auto drain = [&](int round, int tb) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-      const int j = (2 * wave + i) * 64 + lane;
-      const int row = j >> 4;
-      const int cand = round * kRound + row;
-      if (cand < p.C) {
-        const uint4 v = sm.obuf[ob][j];
-        *reinterpret_cast<uint4*>(Ob + int64_t(cand) * row_bytes + ((j & 15) ^ (row & 15)) * 16) = v;
-      }
+      const int q = i * 64 + lane;
+      const int row = q >> 2;
+      const int cand = round * kRound + 32 * half + row;
+      const uint4 v = sm.part[wave][tb][q];
+      if (cand < p.C)
+        *reinterpret_cast<uint4*>(Ob + int64_t(cand) * row_bytes + 64 * hl + ((q & 3) ^ ((row >> 2) & 3)) * 16) = v;
     }
   };
 
-  if (r0 < r1) fill(r0, 0);            // first tile on its way while the operands are set up
+  // ---- the slab of summaries and the first candidate tile are requested together
+#pragma unroll
+  for (int i = 0; i < NKB; ++i) {
+    const int j = (i * kWaves + wave) * 64 + lane;    // slab chunk: row j / 8
+    const int row = j / kRowChunks;                   // < 32 NKB = S
+    dma(&sm.slab[(i * kWaves + wave) * 64], Yb,
+        uint32_t(row) * uint32_t(row_bytes) + uint32_t(((j & (kRowChunks - 1)) ^ ((row >> 1) & (kRowChunks - 1))) * 16));
+  }
+  // the first NB-1 rounds' parts (a round past the end repeats the last one: the count of
+  // loads in flight stays a constant)
+#pragma unroll
+  for (int i = 0; i < NB - 1; ++i) fill(r0 + i < r1 ? r0 + i : r1 - 1, i);
+  wait_vm(Int<2 * (NB - 1)>{});                // the slab has landed (the parts may be on their way)
+  lds_barrier();
 
   // ---- resident operands of this (user, head): K in registers (both waves of the head),
   //      V through the selector MFMA into LDS (each wave builds half of the key blocks)
   bf16x8 kop[NKB][2];
   float kmax2 = 0.f;
   {
-    const uint16_t* Y = p.summ + int64_t(b) * p.S * p.d + 32 * h + 8 * hf;
+    // K operands of all key blocks; they carry the score scale (one extra bf16 rounding of
+    // scale*log2e*k)
+#pragma unroll
+    for (int kb = 0; kb < NKB; ++kb) {
+      const int row = kb * 32 + l32;
+      float n2 = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        Pack8 k, s;
+        k.u = sm.slab[row * kRowChunks + ((4 * hl + 2 * ks + hf) ^ ((row >> 1) & (kRowChunks - 1)))];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          const float a = bf16_lo(k.w[w]), c2 = bf16_hi(k.w[w]);
+          n2 = fmaf(a, a, fmaf(c2, c2, n2));
+          s.w[w] = cvt_pk_bf16(a * p.c, c2 * p.c);
+        }
+        kop[kb][ks] = s.v;
+      }
+      n2 += __shfl_xor(n2, 32, 64);
+      kmax2 = fmaxf(kmax2, n2);
+    }
+#pragma unroll
+    for (int off = 16; off >= 1; off >>= 1) kmax2 = fmaxf(kmax2, __shfl_xor(kmax2, off, 64));
+    kmax2 *= p.c * p.c;
+
+    // V operands: (K block) x (selector) reproduces the block in accumulator layout.  Block
+    // kb of both heads goes exactly where the raw rows of block kb were, so only a
+    // block's own readers have to be done before it is written: up to four blocks per wave
+    // are converted in registers, then a barrier, then their stores.
     Pack8 sel[2];
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
       for (int j = 0; j < 8; ++j) sel[ks].h[j] = (l32 == 16 * ks + 8 * hf + j) ? 0x3F80 : 0;
+    constexpr int NV = (NKB + 1) / 2;            // key blocks whose V operand this wave builds: kb = 2 j + half
 #pragma unroll
-    for (int kb = 0; kb < NKB; ++kb) {
-      Pack8 k[2];
-      float n2 = 0.f;
+    for (int j0 = 0; j0 < NV; j0 += 4) {
+      Pack8 vnew[4][2];
 #pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
-        k[ks].u = *reinterpret_cast<const uint4*>(Y + int64_t(kb * 32 + l32) * p.d + 16 * ks);
+      for (int jj = 0; jj < 4; ++jj) {
+        const int kb = 2 * (j0 + jj) + half;
+        if (j0 + jj < NV && kb < NKB) {
+          const int row = kb * 32 + l32;
+          Pack8 k0, k1;
+          k0.u = sm.slab[row * kRowChunks + ((4 * hl + hf) ^ ((row >> 1) & (kRowChunks - 1)))];
+          k1.u = sm.slab[row * kRowChunks + ((4 * hl + 2 + hf) ^ ((row >> 1) & (kRowChunks - 1)))];
+          f32x16 t = {0};
+          t = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0.v, sel[0].v, t, 0, 0, 0);
+          t = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1.v, sel[1].v, t, 0, 0, 0);
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
-          const float a = bf16_lo(k[ks].w[w]), c2 = bf16_hi(k[ks].w[w]);
-          n2 = fmaf(a, a, fmaf(c2, c2, n2));
+          for (int i = 0; i < 8; i += 2) {
+            vnew[jj][0].w[i / 2] = cvt_pk_bf16(t[i], t[i + 1]);
+            vnew[jj][1].w[i / 2] = cvt_pk_bf16(t[8 + i], t[8 + i + 1]);
+          }
         }
       }
-      n2 += __shfl_xor(n2, 32, 64);
-      kmax2 = fmaxf(kmax2, n2);
-      if ((kb & 1) == half) {
-        // V operand: (K block) x (selector) reproduces the block in accumulator layout
-        f32x16 t = {0};
-        t = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k[0].v, sel[0].v, t, 0, 0, 0);
-        t = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k[1].v, sel[1].v, t, 0, 0, 0);
-        Pack8 v0, v1;
+      lds_barrier();                             // every reader of these blocks' raw rows is done
 #pragma unroll
-        for (int i = 0; i < 8; i += 2) {
-          v0.w[i / 2] = cvt_pk_bf16(t[i], t[i + 1]);
-          v1.w[i / 2] = cvt_pk_bf16(t[8 + i], t[8 + i + 1]);
+      for (int jj = 0; jj < 4; ++jj) {
+        const int kb = 2 * (j0 + jj) + half;
+        if (j0 + jj < NV && kb < NKB) {
+          sm.vop[kb][hl][0][lane] = vnew[jj][0].u;
+          sm.vop[kb][hl][1][lane] = vnew[jj][1].u;
         }
-        sm.vop[hl][kb][0][lane] = v0.u;
-        sm.vop[hl][kb][1][lane] = v1.u;
-      }
-      // K operand carries the score scale (one extra bf16 rounding of scale*log2e*k)
-#pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
-        Pack8 s;
-#pragma unroll
-        for (int w = 0; w < 4; ++w)
-          s.w[w] = cvt_pk_bf16(bf16_lo(k[ks].w[w]) * p.c, bf16_hi(k[ks].w[w]) * p.c);
-        kop[kb][ks] = s.v;
       }
     }
-#pragma unroll
-    for (int off = 16; off >= 1; off >>= 1) kmax2 = fmaxf(kmax2, __shfl_xor(kmax2, off, 64));
-    kmax2 *= p.c * p.c;
   }
 
-  // operand position of this lane inside a tile: row = 32 half + l32, chunk = 4 hl + 2 ks + hf
-  const int orow = 32 * half + l32;
-  const int osw = orow & 15;
+  // operand position of this lane inside its part: row l32, chunk 2 ks + hf
+  const int osw = (l32 >> 2) & 3;
+  lds_barrier();                                 // the V operands of all key blocks are in place
 
+  // Round r lives in buffer (r - r0) mod NB.  Its part was requested NB-1 rounds ago; loads
+  // complete in order among themselves (stores are not ordered with them), so it has landed
+  // once no more operations are outstanding than the loads requested after it.
+  int cur = 0;
   for (int r = r0; r < r1; ++r) {
-    const int cur = (r - r0) & 1;
-    __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0): this wave's part of tile r has landed
-    lds_barrier();                               // ... and everybody else's; obuf[cur] is free again
-    if (r + 1 < r1) fill(r + 1, cur ^ 1);
-    if (r > r0) drain(r - 1, cur ^ 1);
+    const int ahead = r1 - 1 - r;                // rounds after this one
+    if (NB >= 4 && ahead >= 2) wait_vm(Int<4>{});
+    else if (NB >= 3 && ahead >= 1) wait_vm(Int<2>{});
+    else wait_vm(Int<0>{});
+    const int prev = cur == 0 ? NB - 1 : cur - 1;
+    if (r > r0) {
+      drain(r - 1, prev);                        // reads the previous round's buffer into registers, then stores
+      __builtin_amdgcn_s_waitcnt(0xC07F);        // lgkmcnt(0): those reads are done before the buffer is refilled
+    }
+    if (r + NB - 1 < r1) fill(r + NB - 1, prev);
 
     Pack8 c0, c1;
-    c0.u = sm.qbuf[cur][orow * 16 + ((4 * hl + hf) ^ osw)];
-    c1.u = sm.qbuf[cur][orow * 16 + ((4 * hl + 2 + hf) ^ osw)];
+    c0.u = sm.part[wave][cur][l32 * 4 + (hf ^ osw)];
+    c1.u = sm.part[wave][cur][l32 * 4 + ((2 + hf) ^ osw)];
     float qn2 = 0.f;
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
@@ -221,35 +288,51 @@ __global__ __launch_bounds__(512) void attend_mfma_kernel(AttendParams p) {
     qn2 += __shfl_xor(qn2, 32, 64);
     const bool general = __builtin_amdgcn_ballot_w64(qn2 * kmax2 > kSafeBound2) != 0;
     // Key blocks stream through: 32 keys x 32 candidates of scores at a time.  The common
-    // route is straight-line code over all key blocks (one scheduling region).
+    // route is straight-line code over all key blocks (one scheduling region), the scores
+    // of a block computed while the previous block's exponentials run.
     f32x16 o = {0};
-    float l[4] = {0.f, 0.f, 0.f, 0.f};
+    float lsum;
     if (!general) {
+      // The denominator is taken on the matrix core as well: an all-ones A operand makes
+      // every accumulator register the sum of the lane's candidate column over the keys.
+      Pack8 ones;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) ones.w[w] = 0x3F803F80u;
+      f32x16 lacc = {0};
+      f32x16 nx = {0};
+      nx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[0][0], c0.v, nx, 0, 0, 0);
+      nx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[0][1], c1.v, nx, 0, 0, 0);
 #pragma unroll
       for (int kb = 0; kb < NKB; ++kb) {
-        f32x16 sc = {0};
-        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[kb][0], c0.v, sc, 0, 0, 0);
-        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[kb][1], c1.v, sc, 0, 0, 0);
+        const f32x16 sc = nx;
+        if (kb + 1 < NKB) {
+          const f32x16 z = {0};
+          nx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[kb + 1][0], c0.v, z, 0, 0, 0);
+          nx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[kb + 1][1], c1.v, nx, 0, 0, 0);
+        }
         Pack8 v0, v1;
-        v0.u = sm.vop[hl][kb][0][lane];
-        v1.u = sm.vop[hl][kb][1][lane];
+        v0.u = sm.vop[kb][hl][0][lane];
+        v1.u = sm.vop[kb][hl][1][lane];
         Pack8 p0, p1;
 #pragma unroll
         for (int i = 0; i < 16; i += 2) {
           const uint32_t pk = cvt_pk_bf16(__builtin_amdgcn_exp2f(sc[i]), __builtin_amdgcn_exp2f(sc[i + 1]));
-          l[(i / 2) & 3] = dot2_ones(pk, l[(i / 2) & 3]);
           if (i < 8) p0.w[i / 2] = pk; else p1.w[(i - 8) / 2] = pk;
         }
         o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v0.v, p0.v, o, 0, 0, 0);
+        lacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones.v, p0.v, lacc, 0, 0, 0);
         o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v1.v, p1.v, o, 0, 0, 0);
+        lacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones.v, p1.v, lacc, 0, 0, 0);
       }
+      lsum = lacc[0];
     } else {
+      float l[4] = {0.f, 0.f, 0.f, 0.f};
       float m = -INFINITY;
 #pragma unroll 1
       for (int kb = 0; kb < NKB; ++kb) {
         f32x16 sc = {0};
         Pack8 ka, kb2;
-        // dynamic key-block index: operands come back from LDS-free registers through a switch-free path
+        // dynamic key-block index: the operands are picked out of the registers by selects
         ka.v = kop[0][0]; kb2.v = kop[0][1];
 #pragma unroll
         for (int t = 1; t < NKB; ++t)
@@ -257,8 +340,8 @@ __global__ __launch_bounds__(512) void attend_mfma_kernel(AttendParams p) {
         sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka.v, c0.v, sc, 0, 0, 0);
         sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kb2.v, c1.v, sc, 0, 0, 0);
         Pack8 v0, v1;
-        v0.u = sm.vop[hl][kb][0][lane];
-        v1.u = sm.vop[hl][kb][1][lane];
+        v0.u = sm.vop[kb][hl][0][lane];
+        v1.u = sm.vop[kb][hl][1][lane];
         float tmax = sc[0];
 #pragma unroll
         for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, sc[i]);
@@ -280,35 +363,35 @@ __global__ __launch_bounds__(512) void attend_mfma_kernel(AttendParams p) {
         o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v0.v, p0.v, o, 0, 0, 0);
         o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v1.v, p1.v, o, 0, 0, 0);
       }
+      lsum = (l[0] + l[1]) + (l[2] + l[3]);
+      lsum += __shfl_xor(lsum, 32, 64);
     }
-    float lsum = (l[0] + l[1]) + (l[2] + l[3]);
-    lsum += __shfl_xor(lsum, 32, 64);
     const float inv = __builtin_amdgcn_rcpf(lsum);
-    // register group g holds channels 8 g + 4 hf + 0..3 of the head: 8 bytes at chunk 4 hl + g, half hf
+    // register group g holds channels 8 g + 4 hf + 0..3 of the head: 8 bytes at chunk 4 hl + g, half hf.
+    // The results go where this wave's own operands were (nobody else reads those chunks).
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
       uint2 pk;
       pk.x = cvt_pk_bf16(o[4 * g] * inv, o[4 * g + 1] * inv);
       pk.y = cvt_pk_bf16(o[4 * g + 2] * inv, o[4 * g + 3] * inv);
-      reinterpret_cast<uint2*>(&sm.obuf[cur][orow * 16 + ((4 * hl + g) ^ osw)])[hf] = pk;
+      reinterpret_cast<uint2*>(&sm.part[wave][cur][l32 * 4 + (g ^ osw)])[hf] = pk;
     }
+    cur = cur == NB - 1 ? 0 : cur + 1;
   }
-  if (r0 < r1) {
-    lds_barrier();
-    drain(r1 - 1, (r1 - 1 - r0) & 1);
-  }
+  __builtin_amdgcn_s_waitcnt(0xC07F);            // lgkmcnt(0): this wave's last results are in its buffer
+  drain(r1 - 1, cur == 0 ? NB - 1 : cur - 1);
 }
 
 template <int NKB>
 void launch(const AttendParams& p, hipStream_t s) {
-  const unsigned blocks = unsigned(p.B) * unsigned(p.H / 4) * unsigned(p.chunks);
-  hipLaunchKernelGGL(attend_mfma_kernel<NKB>, dim3(blocks), dim3(512), 0, s, p);
+  const unsigned blocks = unsigned(p.B) * unsigned(p.H / kHeads) * unsigned(p.chunks);
+  hipLaunchKernelGGL(attend_mfma_kernel<NKB>, dim3(blocks), dim3(kThreads), 0, s, p);
 }
 
 }  // namespace
 
 bool mfma_target_attend_supported(const vista_attend_desc& d) {
-  return d.dtype == VISTA_BF16 && d.d == 32 * d.H && d.H % 4 == 0 && d.S % 32 == 0 && d.S <= 256 &&
+  return d.dtype == VISTA_BF16 && d.d == 32 * d.H && d.H % kHeads == 0 && d.S % 32 == 0 && (d.S <= 256 || (d.S % 64 == 0 && d.S <= 512)) &&
          int64_t(d.C) * d.d * 2 < (int64_t(1) << 32);
 }
 
@@ -321,15 +404,18 @@ vista_status mfma_target_attend(const vista_attend_desc& d, float scale_log2, co
   p.B = d.B; p.C = d.C; p.S = d.S; p.d = d.d; p.H = d.H;
   p.c = scale_log2;
   // Rounds per workgroup: long enough to amortise the operand set-up (about two rounds'
-  // worth of work), short enough to give the chip >= 512 workgroups.
+  // worth of work), short enough to give the chip two turns of workgroups (256 compute
+  // units x three resident groups, two beyond S = 256).
   const int nrounds = (d.C + kRound - 1) / kRound;
-  const int64_t groups = int64_t(d.B) * (d.H / 4);
+  const int64_t groups = int64_t(d.B) * (d.H / kHeads);
   int per = 8;
-  while (per > 2 && groups * ((nrounds + per - 1) / per) < 512) per >>= 1;
+  const int nkb = d.S / 32;
+  const int64_t want = 256 * 2 * ((nkb <= 6 || nkb == 8) ? 3 : 2);
+  while (per > 2 && groups * ((nrounds + per - 1) / per) < want) per >>= 1;
   p.rounds_per_wg = per;
   p.chunks = (nrounds + per - 1) / per;
   if (groups * p.chunks > 0x7FFFFFFF) return VISTA_ERR_UNSUPPORTED;
-  switch (d.S / 32) {
+  switch (nkb) {
     case 1: launch<1>(p, s); break;
     case 2: launch<2>(p, s); break;
     case 3: launch<3>(p, s); break;
@@ -337,7 +423,12 @@ vista_status mfma_target_attend(const vista_attend_desc& d, float scale_log2, co
     case 5: launch<5>(p, s); break;
     case 6: launch<6>(p, s); break;
     case 7: launch<7>(p, s); break;
-    default: launch<8>(p, s); break;
+    case 8: launch<8>(p, s); break;
+    case 10: launch<10>(p, s); break;
+    case 12: launch<12>(p, s); break;
+    case 14: launch<14>(p, s); break;
+    case 16: launch<16>(p, s); break;
+    default: return VISTA_ERR_UNSUPPORTED;
   }
   VISTA_LAUNCH_CHECK();
   return VISTA_OK;

@@ -28,7 +28,10 @@ def run(T, Y, H):
     (2, 1, 32, 128, 4),         # one candidate, one key block
     (4, 33, 96, 128, 4),        # S = 3 key blocks
     (3, 100, 128, 256, 8),      # 8 heads = two head groups
-    (2, 64, 512, 256, 8),       # S = 512 goes down the plain path
+    (2, 64, 512, 256, 8),       # S = 512: sixteen key blocks, the whole of LDS
+    (3, 200, 512, 128, 4),      # S = 512, several rounds with a ragged tail
+    (2, 130, 320, 128, 4),      # S = 10 key blocks
+    (2, 50, 288, 128, 4),       # S = 9 key blocks goes down the plain path
 ])
 def test_attend_matches_oracle(B, C, S, d, H):
     g = np.random.default_rng(B * 1000 + C)
@@ -49,7 +52,7 @@ def test_attend_large_scores_take_the_true_maximum():
     assert_blocks_close(run(T, Y, H), O.target_attend(T, Y, H), "bf16", "shifted scores")
 
 
-@pytest.mark.parametrize("S,nbits,payload_max", [(256, 8, 200), (32, 5, 3)])
+@pytest.mark.parametrize("S,nbits,payload_max", [(256, 8, 200), (32, 5, 3), (512, 9, 200), (512, 9, 3)])
 def test_attend_selects_the_matching_summary_exactly(S, nbits, payload_max):
     """Indexing, bit-exact: candidate c points at summary token (7c+3+h) mod S through a +-6 code
     of the token index (one differing bit costs 18 bits of weight); the output must be that
