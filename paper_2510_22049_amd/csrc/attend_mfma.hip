@@ -376,6 +376,7 @@ __global__ __launch_bounds__(kThreads, (NKB <= 6 || NKB == 8) ? 3 : 2) void atte
       pk.y = cvt_pk_bf16(o[4 * g + 2] * inv, o[4 * g + 3] * inv);
       reinterpret_cast<uint2*>(&sm.part[wave][cur][l32 * 4 + (g ^ osw)])[hf] = pk;
     }
+    asm volatile("" ::: "memory");   // the 8-byte stores above are read back as 16-byte chunks by the next drain
     cur = cur == NB - 1 ? 0 : cur + 1;
   }
   __builtin_amdgcn_s_waitcnt(0xC07F);            // lgkmcnt(0): this wave's last results are in its buffer
