@@ -37,8 +37,8 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # `rocprofv3 --pmc` runs of this script (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch), each
 # scaled by what the same counter reads for the 1 GiB copy of --calibrate-copy (FETCH_SIZE
 # reads half the bytes on this part: factor 2.0; WRITE_SIZE factor 1.0).
-TRAFFIC_STAGE1_BYTES = (97404.0 * 2.0 + 46704.0) * 1024    # summarize_mfma_kernel: X read once + partial records written
-TRAFFIC_STAGE2_BYTES = (98384.2 * 2.0 + 131072.0) * 1024   # attend_mfma_kernel: candidates + summaries read, outputs written
+TRAFFIC_STAGE1_BYTES = (97092.2 * 2.0 + 45936.0) * 1024    # summarize_mfma_kernel: X read once + partial records written
+TRAFFIC_STAGE2_BYTES = (98383.3 * 2.0 + 131298.9) * 1024   # attend_mfma_kernel: candidates + summaries read, outputs written
 
 
 def bf16_dev(x: np.ndarray) -> torch.Tensor:
