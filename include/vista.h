@@ -147,8 +147,9 @@ typedef struct {
  *   summaries   device [B, S, d]  dtype
  *   out         device [B, C, d]  dtype
  *
- * Supported: bf16 with d/H = 32, H a multiple of 4, S a multiple of 32 up to 256
- * (MFMA path); any dtype with d/H <= 64, S <= 512 (plain path).  No workspace.
+ * Supported: bf16 with d/H = 32, H even, S a multiple of 32 up to 256 or a multiple
+ * of 64 up to 512 (MFMA path); any dtype with d/H <= 64, S <= 512 (plain path).
+ * No workspace.
  */
 vista_status vista_target_attend(const vista_attend_desc* desc,
                                  const void* candidates,
@@ -174,7 +175,8 @@ typedef struct {
  *     out  = (SiLU(yhat W_g) * (yhat W_u)) W_o
  *   y    device [rows, d]     W_g, W_u  device [d, d_ff]    W_o  device [d_ff, d]
  *   out  device [rows, d]     all of dtype
- * Supported: d <= 512, d_ff <= 1024, both multiples of 32.  No workspace.
+ * Supported: d <= 512, d_ff <= 1024, both multiples of 32 (bf16 with d = 128 or 256
+ * runs on the MFMA path, everything else on the plain one).  No workspace.
  */
 vista_status vista_sglu_ffn(const vista_ffn_desc* desc,
                             const void* y,
