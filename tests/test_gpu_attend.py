@@ -32,6 +32,9 @@ def run(T, Y, H):
     (3, 200, 512, 128, 4),      # S = 512, several rounds with a ragged tail
     (2, 130, 320, 128, 4),      # S = 10 key blocks
     (2, 50, 288, 128, 4),       # S = 9 key blocks goes down the plain path
+    (2, 100, 64, 64, 2),        # a single pair of heads
+    (3, 70, 128, 192, 6),       # three head pairs
+    (1, 640, 256, 128, 4),      # one user, ten rounds: several workgroups share the user
 ])
 def test_attend_matches_oracle(B, C, S, d, H):
     g = np.random.default_rng(B * 1000 + C)
