@@ -156,3 +156,19 @@ def test_mfma_agrees_with_plain_path_on_gpu():
                       out32, H=4)
     torch.cuda.synchronize()
     assert block_errors(got, host64(out32)).max() < 2e-2
+
+
+@pytest.mark.parametrize("d,H,S", [(128, 4, 256), (128, 4, 128), (64, 1, 16)])
+def test_degenerate_batches(d, H, S):
+    """No items at all (every user empty), and a batch whose only content is one item."""
+    g = np.random.default_rng(21)
+    Q = bf(g.normal(size=(S, d)))
+    Wk, Wv = bf(g.normal(size=(d, d)) / np.sqrt(d)), bf(g.normal(size=(d, d)) / np.sqrt(d))
+    got = run(np.zeros((0, d), np.float32), [0, 0, 0, 0], Q, Wk, Wv, H)
+    assert got.shape == (3, S, d) and np.all(got == 0)
+    X = bf(g.normal(size=(1, d)))
+    got = run(X, [0, 0, 1, 1], Q, Wk, Wv, H)
+    want = O.summarize(X, [0, 0, 1, 1], Q, Wk, Wv, H)
+    assert np.all(got[0] == 0) and np.all(got[2] == 0)
+    assert_blocks_close(got[1:2], want[1:2], "bf16", "one item")
+    assert np.all(got[1] == got[1][0])          # a single item: every query returns its value row
