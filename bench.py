@@ -33,6 +33,15 @@ from paper_2510_22049_amd import inputs as I
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
+# Second, co-binding bound: the vector ALU's issue port.  Clocks per wave-instruction measured on this
+# part with two waves per SIMD: v_exp_f32 9.75, v_cvt_pk_bf16_f32 / v_add_f32 4.5, and 12 issue clocks
+# per 32x32x16 MFMA.  Per score: one exponential, half a pack, one add (stage 1) and the MFMA issue slots.
+CLOCK_GHZ, SIMDS = 2.4, 256 * 4
+VALU_CLK_STAGE1_TILE = 2 * (24 * 12 + 64 * 9.75 + 40 * 4.5 + 64 * 4.5)     # per 32-item tile and SIMD (two waves)
+VALU_BOUND_STAGE1 = 32 * (SIMDS / 4) / VALU_CLK_STAGE1_TILE * CLOCK_GHZ * 1e9          # items/s at 2.4 GHz
+VALU_CLK_STAGE2_WAVE_ROUND = 48 * 12 + 128 * 9.75 + 64 * 4.5               # 32 candidates x 1 head, S = 256
+VALU_BOUND_STAGE2 = 32 / 4 * SIMDS / VALU_CLK_STAGE2_WAVE_ROUND * CLOCK_GHZ * 1e9      # candidates/s at 2.4 GHz
+
 # HBM bytes per launch of the dominant kernels on exactly these workloads, from two
 # `rocprofv3 --pmc` runs of this script (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch), each
 # scaled by what the same counter reads for the 1 GiB copy of --calibrate-copy (FETCH_SIZE
@@ -183,12 +192,19 @@ def main() -> None:
                      "kernel": "summarize_mfma_kernel<128,4,4>", "flop_per_item": flop_item,
                      "algorithmic_bytes": N * c1.d * 2,
                      "note": "duration = one whole vista_summarize call (plan + summarize_mfma + merge kernels, "
-                             "HIP events on the launch stream); the kernel-only average is in profiles/"},
+                             "HIP events on the launch stream); the kernel-only average is in profiles/",
+                     "co_bound": {"bound": "alu", "what": "VALU issue port (one v_exp_f32 per score)",
+                                  "achieved": items_per_s, "peak": VALU_BOUND_STAGE1, "unit": "items/s",
+                                  "frac": items_per_s / VALU_BOUND_STAGE1, "exp_per_item": c1.S * c1.H}},
         "stage2": {"value": cand_per_s, "unit": "candidate scores/s", "ms_per_step": ms2,
                    "config": {"workload": "stage-2 serving: 1024 users x 512 candidates, S=256, d=128, 4 heads, bf16"},
                    "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                                 "frac": gbs / PEAK_HBM_GBS, "traffic": TRAFFIC_STAGE2_BYTES,
-                                "kernel": "attend_mfma_kernel<8>", "bytes_per_candidate": bytes_cand}},
+                                "kernel": "attend_mfma_kernel<8>", "bytes_per_candidate": bytes_cand,
+                                "co_bound": {"bound": "alu", "what": "VALU issue port (one v_exp_f32 per score)",
+                                             "achieved": cand_per_s, "peak": VALU_BOUND_STAGE2,
+                                             "unit": "candidate scores/s", "frac": cand_per_s / VALU_BOUND_STAGE2,
+                                             "exp_per_candidate": c2.S * c2.H}}},
     }
     if not a.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(host, c1)
