@@ -191,7 +191,7 @@ def main() -> None:
                      "frac": tflops / PEAK_BF16_TFLOPS, "traffic": TRAFFIC_STAGE1_BYTES,
                      "kernel": "summarize_mfma_kernel<128,4,4>", "flop_per_item": flop_item,
                      "algorithmic_bytes": N * c1.d * 2,
-                     "note": "duration = one whole vista_summarize call (plan + summarize_mfma + merge kernels, "
+                     "note": "duration = one whole vista_summarize call (summarize_mfma + merge kernels, "
                              "HIP events on the launch stream); the kernel-only average is in profiles/",
                      "co_bound": {"bound": "alu", "what": "VALU issue port (one v_exp_f32 per score)",
                                   "achieved": items_per_s, "peak": VALU_BOUND_STAGE1, "unit": "items/s",

@@ -89,7 +89,7 @@ struct SummarizeArgs {
   vista_summarize_desc desc;
   int seg;            // resolved segment size
   int64_t G;          // segments
-  const int* seg_user; // [G] first user of each segment (written by the plan kernel)
+  const int* seg_user; // [G] first user of each segment (written by the plan kernel); null: found in the kernel
   float scale_log2;   // scale * log2(e)
   const void* X;
   const int64_t* offsets;

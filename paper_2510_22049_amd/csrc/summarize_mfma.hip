@@ -244,7 +244,7 @@ __device__ __forceinline__ void summarize_wave(const MfmaSummarizeParams& p, Sum
     c.tail = int(len - int64_t(c.tiles_left - 1) * kTile);
   };
   auto cursor_init = [&](Cursor& c) __attribute__((always_inline)) {
-    c.wuser = __builtin_amdgcn_readfirstlane(p.seg_user[g]);
+    c.wuser = p.seg_user ? __builtin_amdgcn_readfirstlane(p.seg_user[g]) : find_user(p.offsets, p.B, seg_begin);
     c.wpos = seg_begin;
     Piece pc;
     pc.user = 0;
@@ -534,8 +534,10 @@ __global__ __launch_bounds__(HPW * 128) void summarize_mfma_kernel(MfmaSummarize
 __global__ __launch_bounds__(256) void merge_mfma_kernel(const float* __restrict__ partials,
                                                          const int64_t* __restrict__ offsets, int S, int d,
                                                          int H, int seg, int64_t G,
-                                                         uint16_t* __restrict__ out) {
+                                                         uint16_t* __restrict__ out, int* status) {
   const int qb = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  // without a plan kernel in front (offsets checked on the host) the status word is cleared here
+  if (status && qb == 0 && h == 0 && b == 0 && threadIdx.x == 0) *status = VISTA_OK;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int hf = lane >> 5, l32 = lane & 31;
   const int64_t begin = offsets[b], end = offsets[b + 1];
@@ -659,7 +661,8 @@ vista_status mfma_summarize(const SummarizeArgs& a) {
     VISTA_LAUNCH_CHECK();
   }
   hipLaunchKernelGGL(merge_mfma_kernel, dim3(d.S / 32, d.H, d.B), dim3(256), 0, a.stream, p.partials, a.offsets,
-                     d.S, d.d, d.H, a.seg, a.G, static_cast<uint16_t*>(a.out));
+                     d.S, d.d, d.H, a.seg, a.G, static_cast<uint16_t*>(a.out),
+                     a.seg_user ? nullptr : reinterpret_cast<int*>(a.workspace));
   VISTA_LAUNCH_CHECK();
   return VISTA_OK;
 }

@@ -99,6 +99,12 @@ vista_status vista_summarize(const vista_summarize_desc* desc, const void* histo
   a.workspace = static_cast<char*>(workspace);
   a.stream = static_cast<hipStream_t>(hip_stream);
 
+  // Offsets already checked on the host: the MFMA path finds each segment's first user
+  // itself and its merge kernel clears the status word, so the plan kernel is not needed.
+  if (offsets_host && mfma_summarize_supported(*desc)) {
+    a.seg_user = nullptr;
+    return mfma_summarize(a);
+  }
   int* seg_user = reinterpret_cast<int*>(a.workspace + kHeaderBytes);
   a.seg_user = seg_user;
   launch_plan(offsets, desc->B, desc->total_items, a.seg, a.G, reinterpret_cast<int*>(workspace), seg_user, a.stream);
