@@ -130,7 +130,7 @@ __global__ __launch_bounds__(kThreads, (NKB <= 6 || NKB == 8) ? 3 : 2) void atte
   auto dma = [&](const uint4* dst, const char* base, uint32_t voff) __attribute__((always_inline)) {
     const uint32_t lds_base =
         uint32_t(reinterpret_cast<uintptr_t>((void __attribute__((address_space(3)))*)(dst)));
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
                  : "s"(lds_base), "v"(voff), "s"(base)
                  : "memory", "m0");

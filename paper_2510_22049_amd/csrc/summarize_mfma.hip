@@ -300,7 +300,7 @@ __device__ __forceinline__ void summarize_wave(const MfmaSummarizeParams& p, Sum
       // the end of the next tile, not a conservative one before the next LDS read.
       const uint32_t lds_base = uint32_t(reinterpret_cast<uintptr_t>(
           (void __attribute__((address_space(3)))*)(&sm.xbuf[xb][k * NT + wave * 64])));
-      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                    :
                    : "s"(lds_base), "v"(voff), "s"(base)
                    : "memory", "m0");
