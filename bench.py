@@ -35,11 +35,11 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
 # Second, co-binding bound: the vector ALU's issue port.  Clocks per wave-instruction measured on this
 # part with two waves per SIMD: v_exp_f32 9.75, v_cvt_pk_bf16_f32 / v_add_f32 4.5, and 12 issue clocks
-# per 32x32x16 MFMA.  Per score: one exponential, half a pack, one add (stage 1) and the MFMA issue slots.
+# per 32x32x16 MFMA.  Per score: one exponential, half a pack, one add and the MFMA issue slots.
 CLOCK_GHZ, SIMDS = 2.4, 256 * 4
 VALU_CLK_STAGE1_TILE = 2 * (24 * 12 + 64 * 9.75 + 40 * 4.5 + 64 * 4.5)     # per 32-item tile and SIMD (two waves)
 VALU_BOUND_STAGE1 = 32 * (SIMDS / 4) / VALU_CLK_STAGE1_TILE * CLOCK_GHZ * 1e9          # items/s at 2.4 GHz
-VALU_CLK_STAGE2_WAVE_ROUND = 48 * 12 + 128 * 9.75 + 64 * 4.5               # 32 candidates x 1 head, S = 256
+VALU_CLK_STAGE2_WAVE_ROUND = 32 * 12 + 128 * 9.75 + 64 * 4.5 + 128 * 4.5   # 32 candidates x 1 head, S = 256
 VALU_BOUND_STAGE2 = 32 / 4 * SIMDS / VALU_CLK_STAGE2_WAVE_ROUND * CLOCK_GHZ * 1e9      # candidates/s at 2.4 GHz
 
 # HBM bytes per launch of the dominant kernels on exactly these workloads, from two

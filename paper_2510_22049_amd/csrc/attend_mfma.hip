@@ -293,12 +293,10 @@ __global__ __launch_bounds__(kThreads, (NKB <= 6 || NKB == 8) ? 3 : 2) void atte
     f32x16 o = {0};
     float lsum;
     if (!general) {
-      // The denominator is taken on the matrix core as well: an all-ones A operand makes
-      // every accumulator register the sum of the lane's candidate column over the keys.
-      Pack8 ones;
-#pragma unroll
-      for (int w = 0; w < 4; ++w) ones.w[w] = 0x3F803F80u;
-      f32x16 lacc = {0};
+      // The denominator adds the weights before their rounding to bf16: plain adds run beside
+      // the matrix core (the packed dot product does not, and taking the sums with an all-ones
+      // MFMA operand measured 3 % slower than the adds).
+      float l[4] = {0.f, 0.f, 0.f, 0.f};
       f32x16 nx = {0};
       nx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[0][0], c0.v, nx, 0, 0, 0);
       nx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[0][1], c1.v, nx, 0, 0, 0);
@@ -316,15 +314,16 @@ __global__ __launch_bounds__(kThreads, (NKB <= 6 || NKB == 8) ? 3 : 2) void atte
         Pack8 p0, p1;
 #pragma unroll
         for (int i = 0; i < 16; i += 2) {
-          const uint32_t pk = cvt_pk_bf16(__builtin_amdgcn_exp2f(sc[i]), __builtin_amdgcn_exp2f(sc[i + 1]));
+          const float ea = __builtin_amdgcn_exp2f(sc[i]), eb = __builtin_amdgcn_exp2f(sc[i + 1]);
+          const uint32_t pk = cvt_pk_bf16(ea, eb);
+          l[(i / 2) & 3] += ea + eb;
           if (i < 8) p0.w[i / 2] = pk; else p1.w[(i - 8) / 2] = pk;
         }
         o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v0.v, p0.v, o, 0, 0, 0);
-        lacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones.v, p0.v, lacc, 0, 0, 0);
         o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v1.v, p1.v, o, 0, 0, 0);
-        lacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones.v, p1.v, lacc, 0, 0, 0);
       }
-      lsum = lacc[0];
+      lsum = (l[0] + l[1]) + (l[2] + l[3]);
+      lsum += __shfl_xor(lsum, 32, 64);
     } else {
       float l[4] = {0.f, 0.f, 0.f, 0.f};
       float m = -INFINITY;
