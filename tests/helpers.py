@@ -33,3 +33,15 @@ def assert_blocks_close(got, want, dtype, what=""):
     worst = int(err.argmax())
     assert err[worst] <= TOL[dtype], f"{what}: block {worst} error {err[worst]:.3e} > {TOL[dtype]:.0e}"
     return float(err.max())
+
+
+def assert_in_value_hull(out: torch.Tensor, values: torch.Tensor, what="", slack=2.0 ** -7):
+    """Property that holds at any size: softmax weights are non-negative and sum to one, so every
+    output channel of a block lies between the smallest and the largest value of that channel
+    (out [..., rows, d] against values [..., n, d], compared on the device in fp32; `slack` x the
+    channel's largest magnitude allows for the bf16 roundings of values, weights and output)."""
+    v = values.float()
+    lo, hi = v.amin(dim=-2, keepdim=True), v.amax(dim=-2, keepdim=True)
+    tol = slack * torch.maximum(lo.abs(), hi.abs())
+    o = out.float()
+    assert bool(((o >= lo - tol) & (o <= hi + tol)).all()), f"{what}: output outside the hull of its values"

@@ -6,7 +6,7 @@ import torch
 from oracle import vista_oracle as O
 from paper_2510_22049_amd import binding as V
 from paper_2510_22049_amd import inputs as I
-from tests.helpers import assert_blocks_close, dev, host64
+from tests.helpers import assert_blocks_close, assert_in_value_hull, dev, host64
 
 pytestmark = pytest.mark.gpu
 
@@ -108,6 +108,9 @@ def test_config4_sampled_users():
     V.vista_target_attend(T, Y, out, H=c.H)
     torch.cuda.synchronize()
     assert bool(torch.isfinite(out.float()).all())
+    for h in range(c.H):                             # every user: outputs inside the hull of the head's summaries
+        sl = slice(32 * h, 32 * h + 32)
+        assert_in_value_hull(out[:, :, sl], Y[:, :, sl], f"config 4 head {h}")
     got = host64(out[users])
     want = O.target_attend(np.stack([I.candidates_user(c, u) for u in users]),
                            np.stack([I.summaries_user(c, u) for u in users]), c.H)

@@ -12,7 +12,7 @@ import torch
 from oracle import vista_oracle as O
 from paper_2510_22049_amd import binding as V
 from paper_2510_22049_amd import inputs as I
-from tests.helpers import assert_blocks_close, dev, host64
+from tests.helpers import assert_blocks_close, assert_in_value_hull, dev, host64
 
 pytestmark = pytest.mark.gpu
 
@@ -30,6 +30,15 @@ def history_on_device(c, lens):
         for b, t in ex.map(one, range(len(lens))):
             X[off[b]:off[b + 1]] = t.cuda().view(torch.bfloat16)
     return X, off
+
+
+def assert_summaries_in_hull(out, X, off, Wv, what):
+    """Every user, any size: a summary channel lies inside the range of that channel of the user's
+    values X_b W_v (formed here with a library matmul in fp32)."""
+    W = Wv.float()
+    for b in range(len(off) - 1):
+        if off[b + 1] > off[b]:
+            assert_in_value_hull(out[b], X[off[b]:off[b + 1]].float() @ W, f"{what} user {b}")
 
 
 def summarize(X, off, Q, Wk, Wv, H):
@@ -50,6 +59,7 @@ def test_config2_jagged_batch_all_users():
     X, off = history_on_device(c, lens)
     Q, Wk, Wv = I.virtual_queries(c), I.projection(c, "W_k"), I.projection(c, "W_v")
     out = summarize(X, off, dev(Q, "bf16"), dev(Wk, "bf16"), dev(Wv, "bf16"), c.H)
+    assert_summaries_in_hull(out, X, off, dev(Wv, "bf16"), "config 2")
     got = host64(out)
     want = np.zeros_like(got)
     for b in range(c.B):
@@ -66,6 +76,7 @@ def test_config3_lifelong_sampled_queries():
     X, off = history_on_device(c, lens)
     Q, Wk, Wv = I.virtual_queries(c), I.projection(c, "W_k"), I.projection(c, "W_v")
     out = summarize(X, off, dev(Q, "bf16"), dev(Wk, "bf16"), dev(Wv, "bf16"), c.H)
+    assert_summaries_in_hull(out, X, off, dev(Wv, "bf16"), "config 3")
     rows = np.array([0, 1, 31, 32, 63, 64, 100, 127, 128, 129, 191, 200, 222, 254, 255, 77])
     got = host64(out[:, torch.from_numpy(rows).cuda()])
     for b in (0, 3, 7):
@@ -100,6 +111,9 @@ def test_config5_end_to_end_sampled_users():
     torch.cuda.synchronize()
     for t in (q1, out):
         assert bool(torch.isfinite(t.float()).all())
+    assert_summaries_in_hull(y1, X, off, dev(W["W_v0"], "bf16"), "config 5 layer 1")      # all 256 users
+    assert_summaries_in_hull(y2, X, off, dev(W["W_v1"], "bf16"), "config 5 layer 2")
+    assert_in_value_hull(out, y2, "config 5 stage 2")
     rows = np.arange(0, c.S, 16)                       # 32 sampled query rows of each layer
     for u in users:
         Xu = I.history_user(c, u, int(lens[u]))
