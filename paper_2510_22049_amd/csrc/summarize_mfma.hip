@@ -15,6 +15,9 @@
 // the projected K^T / V accumulators already are the next MFMA's A operand.
 // The projection of tile t+1 rides along with the attention over tile t, and
 // the tiles of all pieces (user x segment) of the segment form one stream.
+// Where a pair would leave a wave with more than four query blocks (S = 512) or
+// with too few waves per compute unit (D = 256), a head gets four waves instead:
+// the K and V waves plus two that only attend, a quarter of the queries each.
 //
 // Softmax reference.  Scores are kept in base-2 units.  While every score of a
 // tile is provably inside [-60, 60] (Cauchy-Schwarz: |q| |k| <= 60) the
@@ -148,15 +151,19 @@ struct SummarizeLds {
   uint4 wop[HPW][2][D / 16][64];      // projection weights as MFMA operands: [head][K|V][k-slice][lane]
 };
 
-// Body of one wave; ROLE 0 forms K^T, ROLE 1 forms V.  The tile loop is
+// Body of one wave; ROLE 0 forms K^T, ROLE 1 forms V, ROLE 2 forms nothing and only attends
+// (the third and fourth wave of a head when its queries are spread over four waves: WPH = 4).  The tile loop is
 // software-pipelined: while the wave attends over tile t (VALU-heavy) it also
 // issues the projection MFMAs of tile t+1, and the X rows of tiles t+2 / t+3 are
 // on their way from HBM (registers) into the LDS buffer tile t has vacated.  One
 // LDS-only barrier per tile orders the two double-buffered exchanges.
-template <int D, int NQB, int HPW, int ROLE>
+template <int D, int NQB, int HPW, int ROLE, int WPH = 2>
 __device__ __forceinline__ void summarize_wave(const MfmaSummarizeParams& p, SummarizeLds<D, HPW>& sm,
-                                               int64_t g, int h, int hl, int64_t seg_begin, int64_t seg_end) {
-  constexpr int NT = HPW * 128;          // threads
+                                               int64_t g, int h, int hl, int qslot, int64_t seg_begin,
+                                               int64_t seg_end) {
+  constexpr bool PROJ = ROLE < 2;        // this wave projects
+  constexpr int WR = PROJ ? ROLE : 0;    // its slot in the weight and K/V buffers (unused otherwise)
+  constexpr int NT = HPW * WPH * 64;     // threads
   constexpr int CH = D / 8;              // 16-byte chunks per row
   constexpr int KS = D / 16;             // k-slices of the projection
   constexpr int CPT = kTile * CH / NT;   // X chunks a thread moves per tile
@@ -174,7 +181,7 @@ __device__ __forceinline__ void summarize_wave(const MfmaSummarizeParams& p, Sum
   // registers go to the accumulators instead).  Element j of slice ks is
   // W[16 ks + 8 hf + j][32 h + l32]; the key weights carry scale*log2(e), so the
   // scores leave the MFMA in base-2 units.
-  {
+  if constexpr (PROJ) {
     const uint16_t* W = ROLE ? p.Wv : p.Wk;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
@@ -184,11 +191,11 @@ __device__ __forceinline__ void summarize_wave(const MfmaSummarizeParams& p, Sum
         const uint16_t w = W[(16 * ks + 8 * hf + j) * D + 32 * h + l32];
         t.h[j] = ROLE ? w : f32_to_bf16_bits(__uint_as_float(uint32_t(w) << 16) * p.c);
       }
-      sm.wop[hl][ROLE][ks][lane] = t.u;
+      sm.wop[hl][WR][ks][lane] = t.u;
     }
   }
 
-  const int qbase = ROLE * (NQB * 32);   // first query of this wave
+  const int qbase = qslot * (NQB * 32);  // first query of this wave (qslot = ROLE when a head has two waves)
   bf16x8 qop[NQB][2];
   float qmax2 = 0.f;
   auto load_queries = [&](int user) __attribute__((always_inline)) {
@@ -308,28 +315,32 @@ __device__ __forceinline__ void summarize_wave(const MfmaSummarizeParams& p, Sum
   };
   // k-slices [ks0, ks1) of this wave's projection of the X tile in xbuf[buf]
   auto project = [&](int buf, int ks0, int ks1, f32x16& acc) __attribute__((always_inline)) {
+    if constexpr (PROJ) {
 #pragma unroll
-    for (int ks = ks0; ks < ks1; ++ks) {
-      Pack8 x, w;
-      x.u = sm.xbuf[buf][(2 * ks + hf) * 32 + l32];
-      w.u = sm.wop[hl][ROLE][ks][lane];
-      acc = ROLE ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(x.v, w.v, acc, 0, 0, 0)
-                 : __builtin_amdgcn_mfma_f32_32x32x16_bf16(w.v, x.v, acc, 0, 0, 0);
+      for (int ks = ks0; ks < ks1; ++ks) {
+        Pack8 x, w;
+        x.u = sm.xbuf[buf][(2 * ks + hf) * 32 + l32];
+        w.u = sm.wop[hl][WR][ks][lane];
+        acc = ROLE ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(x.v, w.v, acc, 0, 0, 0)
+                   : __builtin_amdgcn_mfma_f32_32x32x16_bf16(w.v, x.v, acc, 0, 0, 0);
+      }
     }
   };
   // hand the projected tile to the partner wave: bf16 operand halves (+ key norms)
   auto publish = [&](int buf, const f32x16& acc) __attribute__((always_inline)) {
-    Pack8 r0, r1;
-    float n2 = 0.f;
+    if constexpr (PROJ) {
+      Pack8 r0, r1;
+      float n2 = 0.f;
 #pragma unroll
-    for (int i = 0; i < 16; i += 2) {
-      const uint32_t pk = cvt_pk_bf16(acc[i], acc[i + 1]);
-      if (ROLE == 0) n2 = dot2_self(pk, n2);
-      if (i < 8) r0.w[i / 2] = pk; else r1.w[(i - 8) / 2] = pk;
+      for (int i = 0; i < 16; i += 2) {
+        const uint32_t pk = cvt_pk_bf16(acc[i], acc[i + 1]);
+        if (ROLE == 0) n2 = dot2_self(pk, n2);
+        if (i < 8) r0.w[i / 2] = pk; else r1.w[(i - 8) / 2] = pk;
+      }
+      sm.kvbuf[buf][hl][WR][0][lane] = r0.u;
+      sm.kvbuf[buf][hl][WR][1][lane] = r1.u;
+      if (ROLE == 0) sm.knorm[buf][hl][lane] = n2;
     }
-    sm.kvbuf[buf][hl][ROLE][0][lane] = r0.u;
-    sm.kvbuf[buf][hl][ROLE][1][lane] = r1.u;
-    if (ROLE == 0) sm.knorm[buf][hl][lane] = n2;
   };
   auto unsafe_tile = [&](int buf) __attribute__((always_inline)) {
     const float kn2 = sm.knorm[buf][hl][lane] + sm.knorm[buf][hl][lane ^ 32];
@@ -522,9 +533,38 @@ __global__ __launch_bounds__(HPW * 128) void summarize_mfma_kernel(MfmaSummarize
   const int64_t seg_end = (seg_begin + p.seg < p.N) ? seg_begin + p.seg : p.N;
   // Both roles run the same sequence of barriers; only the MFMA operand order differs.
   if (wave & 1)
-    summarize_wave<D, NQB, HPW, 1>(p, sm, g, h, hl, seg_begin, seg_end);
+    summarize_wave<D, NQB, HPW, 1>(p, sm, g, h, hl, 1, seg_begin, seg_end);
   else
-    summarize_wave<D, NQB, HPW, 0>(p, sm, g, h, hl, seg_begin, seg_end);
+    summarize_wave<D, NQB, HPW, 0>(p, sm, g, h, hl, 0, seg_begin, seg_end);
+}
+
+// Four waves per head (two heads per workgroup): the K and V waves project as above, two more
+// waves only attend, each of the four with a quarter of the queries.  With S = 512 this keeps a
+// wave at 4 query blocks, i.e. inside 256 vector registers and at two waves per SIMD.  Wave
+// w serves head w / 4 in slot (w + 2 (w / 4)) % 4, so that each SIMD (wave id mod 4) gets one
+// projecting and one attend-only wave.
+template <int D, int NQB>
+__global__ __launch_bounds__(512) void summarize_mfma4_kernel(MfmaSummarizeParams p) {
+  constexpr int HPW = 2;
+  __shared__ SummarizeLds<D, HPW> sm;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int hl = wave >> 2;
+  const int slot = (wave + 2 * hl) & 3;
+  const int64_t id = blockIdx.x;
+  const int64_t grp = id / (8 * p.nhg);
+  const int idl = int(id - grp * 8 * p.nhg);
+  const int64_t g = grp * 8 + (idl & 7);
+  const int hg = idl >> 3;
+  const int h = hg * HPW + hl;
+  const int64_t seg_begin = g * p.seg;
+  if (seg_begin >= p.N) return;          // padding blocks of the last group (whole workgroup)
+  const int64_t seg_end = (seg_begin + p.seg < p.N) ? seg_begin + p.seg : p.N;
+  if (slot == 0)
+    summarize_wave<D, NQB, HPW, 0, 4>(p, sm, g, h, hl, 0, seg_begin, seg_end);
+  else if (slot == 1)
+    summarize_wave<D, NQB, HPW, 1, 4>(p, sm, g, h, hl, 1, seg_begin, seg_end);
+  else
+    summarize_wave<D, NQB, HPW, 2, 4>(p, sm, g, h, hl, slot, seg_begin, seg_end);
 }
 
 // Merge of a user's partial records, ascending segment order (fixed, so the
@@ -609,6 +649,13 @@ size_t mfma_summarize_workspace(const vista_summarize_desc& d, int seg) {
   return kHeaderBytes + plan_bytes(G) + ((partial_bytes(d, seg) + 255) & ~size_t(255));
 }
 
+template <int D, int NQB>
+static void launch_main4(const MfmaSummarizeParams& p, int64_t G, hipStream_t s) {
+  const int64_t groups = (G + 7) / 8;
+  const int64_t blocks = groups * 8 * p.nhg;
+  hipLaunchKernelGGL((summarize_mfma4_kernel<D, NQB>), dim3(unsigned(blocks)), dim3(512), 0, s, p);
+}
+
 template <int D, int NQB, int HPW>
 static void launch_main(const MfmaSummarizeParams& p, int64_t G, hipStream_t s) {
   const int64_t groups = (G + 7) / 8;
@@ -646,16 +693,16 @@ vista_status mfma_summarize(const SummarizeArgs& a) {
           break;
         default:
           p.nhg = 2;
-          launch_main<128, 8, 2>(p, a.G, a.stream);
+          launch_main4<128, 4>(p, a.G, a.stream);
           break;
       }
     } else {
       p.nhg = 4;
       switch (d.S) {
         case 64: launch_main<256, 1, 2>(p, a.G, a.stream); break;
-        case 128: launch_main<256, 2, 2>(p, a.G, a.stream); break;
-        case 256: launch_main<256, 4, 2>(p, a.G, a.stream); break;
-        default: launch_main<256, 8, 2>(p, a.G, a.stream); break;
+        case 128: launch_main4<256, 1>(p, a.G, a.stream); break;
+        case 256: launch_main4<256, 2>(p, a.G, a.stream); break;
+        default: launch_main4<256, 4>(p, a.G, a.stream); break;
       }
     }
     VISTA_LAUNCH_CHECK();

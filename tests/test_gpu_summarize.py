@@ -38,7 +38,8 @@ def problem(seed, lens, d, S, per_user=False, xscale=1.0):
 LENS = [700, 0, 1, 31, 32, 33, 2100, 64, 0, 95, 1029]
 
 
-@pytest.mark.parametrize("d,H,S", [(128, 4, 256), (128, 4, 64), (128, 4, 512), (256, 8, 512), (256, 8, 128)])
+@pytest.mark.parametrize("d,H,S", [(128, 4, 256), (128, 4, 64), (128, 4, 128), (128, 4, 512), (256, 8, 512), (256, 8, 256),
+                                   (256, 8, 128), (256, 8, 64)])
 @pytest.mark.parametrize("seg", [0, 64, 992])
 def test_mfma_jagged_matches_oracle(d, H, S, seg):
     """Empty, single-item, one-tile, ragged and multi-segment users; shared queries."""
