@@ -279,11 +279,12 @@ __global__ __launch_bounds__(kThreads, (NKB <= 6 || NKB == 8) ? 3 : 2) void atte
     Pack8 c0, c1;
     c0.u = sm.part[wave][cur][l32 * 4 + (hf ^ osw)];
     c1.u = sm.part[wave][cur][l32 * 4 + ((2 + hf) ^ osw)];
-    float qn2 = 0.f;
+    float qn2 = 0.f;                             // squared norm of the candidate's head slice (packed dot products)
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
-      const float a0 = bf16_lo(c0.w[w]), a1 = bf16_hi(c0.w[w]), b0 = bf16_lo(c1.w[w]), b1 = bf16_hi(c1.w[w]);
-      qn2 = fmaf(a0, a0, fmaf(a1, a1, fmaf(b0, b0, fmaf(b1, b1, qn2))));
+      const bf16x2 a = __builtin_bit_cast(bf16x2, c0.w[w]), b2 = __builtin_bit_cast(bf16x2, c1.w[w]);
+      qn2 = __builtin_amdgcn_fdot2_f32_bf16(a, a, qn2, false);
+      qn2 = __builtin_amdgcn_fdot2_f32_bf16(b2, b2, qn2, false);
     }
     qn2 += __shfl_xor(qn2, 32, 64);
     const bool general = __builtin_amdgcn_ballot_w64(qn2 * kmax2 > kSafeBound2) != 0;
