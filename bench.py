@@ -46,8 +46,8 @@ VALU_BOUND_STAGE2 = 32 / 4 * SIMDS / VALU_CLK_STAGE2_WAVE_ROUND * CLOCK_GHZ * 1e
 # `rocprofv3 --pmc` runs of this script (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch), each
 # scaled by what the same counter reads for the 1 GiB copy of --calibrate-copy (FETCH_SIZE
 # reads half the bytes on this part: factor 2.0; WRITE_SIZE factor 1.0).
-TRAFFIC_STAGE1_BYTES = (97113.0 * 2.0 + 45936.0) * 1024    # summarize_mfma_kernel: X read once + partial records written
-TRAFFIC_STAGE2_BYTES = (98398.2 * 2.0 + 131531.0) * 1024   # attend_mfma_kernel: candidates + summaries read, outputs written
+TRAFFIC_STAGE1_BYTES = (97112.4 * 2.0 + 45936.0) * 1024    # summarize_mfma_kernel: X read once + partial records written
+TRAFFIC_STAGE2_BYTES = (98387.2 * 2.0 + 131569.9) * 1024   # attend_mfma_kernel: candidates + summaries read, outputs written
 
 
 def bf16_dev(x: np.ndarray) -> torch.Tensor:
