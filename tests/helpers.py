@@ -27,6 +27,17 @@ def block_errors(got: np.ndarray, want: np.ndarray) -> np.ndarray:
     return np.abs(g - w).max(axis=1) / den
 
 
+def floored_errors(got: np.ndarray, want: np.ndarray, floor: float = 1e-3) -> np.ndarray:
+    """Element-wise |got - want| / max(|want|, floor x the block's max |want|), worst element per block.
+    Reported as information only: near-zero, sign-changing outputs make a bare element-wise ratio
+    meaningless, the floor keeps it finite."""
+    g = got.reshape(got.shape[0], -1)
+    w = want.reshape(want.shape[0], -1)
+    top = np.abs(w).max(axis=1, keepdims=True)
+    den = np.maximum(np.abs(w), floor * np.where(top == 0, 1.0, top))
+    return (np.abs(g - w) / den).max(axis=1)
+
+
 def assert_blocks_close(got, want, dtype, what=""):
     assert np.all(np.isfinite(got)), f"{what}: non-finite output"
     err = block_errors(got, want)

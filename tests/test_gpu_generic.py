@@ -67,6 +67,23 @@ def test_generic_jagged_shapes(dtype, H, d, S):
     assert_blocks_close(run_attend(T, Y, H, dtype), O.target_attend(T, Y, H), dtype, "generic stage 2")
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_generic_scale_override(dtype):
+    """A non-default score scale on the plain path, both stages."""
+    g = np.random.default_rng(17)
+    lens, d, S, H = [90, 0, 300], 64, 24, 2
+    off = I.offsets_from_lengths(lens)
+    rnd = lambda shape, s=1.0: I.round_to((g.normal(size=shape) * s).astype(np.float32), dtype)
+    X, Q, Wk, Wv = rnd((off[-1], d)), rnd((S, d)), rnd((d, d), d ** -0.5), rnd((d, d), d ** -0.5)
+    got = run_summarize(X, off, Q, Wk, Wv, H, dtype, scale=0.6)
+    assert_blocks_close(got, O.summarize(X, off, Q, Wk, Wv, H, scale=0.6), dtype, "plain stage 1, scale 0.6")
+    T, Y = rnd((2, 9, d)), rnd((2, S, d))
+    out = torch.full(T.shape, float("nan"), device="cuda", dtype=torch_dtype(dtype))
+    V.vista_target_attend(dev(T, dtype), dev(Y, dtype), out, H=H, scale=0.6)
+    torch.cuda.synchronize()
+    assert_blocks_close(host64(out), O.target_attend(T, Y, H, scale=0.6), dtype, "plain stage 2, scale 0.6")
+
+
 def test_generic_exact_integer_indexing():
     """Q = 0, W_v = I, integer X: out * L_b must be the exact column sums of user b's rows."""
     lens = [7, 0, 33, 1, 64, 200, 95]

@@ -57,6 +57,17 @@ def test_mfma_per_user_queries(d, H, S):
     assert_blocks_close(got, O.summarize(X, off, Q, Wk, Wv, H), "bf16", "per-user queries")
 
 
+@pytest.mark.parametrize("d,H,S", [(128, 4, 256), (256, 8, 512)])
+@pytest.mark.parametrize("scale", [0.03, 0.5])
+def test_mfma_scale_override(d, H, S, scale):
+    """A non-default score scale reaches the kernel (it is folded into the key weights)."""
+    X, off, Q, Wk, Wv = problem(8, [700, 0, 33, 1300], d, S)
+    got = run(X, off, Q, Wk, Wv, H, segment_items=256, scale=scale)
+    want = O.summarize(X, off, Q, Wk, Wv, H, scale=scale)
+    assert_blocks_close(got, want, "bf16", f"scale={scale}")
+    assert block_errors(O.summarize(X, off, Q, Wk, Wv, H)[[0, 3]], want[[0, 3]]).max() > 5e-2   # the override matters
+
+
 def test_mfma_large_scores_mix_both_softmax_routes():
     """Item norms straddle the bound |q||k| <= 60 (base 2): tiles switch from the constant
     reference to the running maximum inside a piece."""
@@ -138,8 +149,8 @@ def test_mfma_is_bitwise_reproducible_and_isolated():
     """Same inputs -> same bits; poisoning one user's rows leaves the others' bits unchanged."""
     X, off, Q, Wk, Wv = problem(6, [500, 260, 1200, 33], 128, 256)
     a = run(X, off, Q, Wk, Wv, 4, segment_items=256)
-    b = run(X, off, Q, Wk, Wv, 4, segment_items=256)
-    assert np.array_equal(a, b)
+    for _ in range(5):
+        assert np.array_equal(a, run(X, off, Q, Wk, Wv, 4, segment_items=256))
     X2 = X.copy()
     X2[off[1]:off[2]] = bf(X2[off[1]:off[2]] * 3 + 1)
     c = run(X2, off, Q, Wk, Wv, 4, segment_items=256)
