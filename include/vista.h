@@ -19,7 +19,10 @@
  *     given hipStream_t (passed as void*; NULL is the default stream).
  *   - Inputs are read-only; outputs are fully overwritten.
  *   - Errors are return codes.  Everything that can be checked on the host is
- *     checked before the first launch; on a non-zero return nothing was enqueued.
+ *     checked before the first launch: on any status but VISTA_ERR_HIP nothing
+ *     was enqueued.  VISTA_ERR_HIP reports that the runtime refused one of the
+ *     call's launches; kernels launched before it may already be enqueued and the
+ *     outputs are then undefined.
  *   - 64-bit row addressing throughout: N * d may exceed 2^31.
  */
 #ifndef VISTA_H
@@ -39,7 +42,7 @@ typedef enum {
   VISTA_ERR_OFFSETS = 3,     /* offsets_host: not starting at 0, decreasing, or not ending at total_items */
   VISTA_ERR_UNSUPPORTED = 4, /* dtype / head width / S outside the supported set */
   VISTA_ERR_WORKSPACE = 5,   /* workspace pointer NULL, misaligned or too small */
-  VISTA_ERR_HIP = 6          /* a launch failed; hipGetLastError() has the cause */
+  VISTA_ERR_HIP = 6          /* the runtime refused a kernel launch of this call */
 } vista_status;
 
 /* storage dtype of every tensor of a call; accumulation is always fp32 */
@@ -82,6 +85,23 @@ typedef struct {
  */
 int32_t vista_summarize_segment_items(const vista_summarize_desc* desc);
 
+/*
+ * The schedule itself, computed on the host by the very code the kernels run
+ * (App. B: blocks of the history are summed first, in any grouping; this is the
+ * grouping).  Every segment is walked as a stream of tiles of at most 32 rows;
+ * a tile never spans two users.  Writes up to max_tiles records
+ *     tiles[4 i + 0..3] = { segment, user, first flat row, rows in the tile (1..32) }
+ * in the order the kernels visit them and returns the total number of tiles
+ * (which may exceed max_tiles; pass max_tiles = 0, tiles = NULL to count), or -1
+ * for an invalid descriptor or a NULL offsets_host.  offsets_host is NOT
+ * validated here: for valid offsets the tiles cover every row of every user
+ * exactly once; for any other contents every tile still lies inside
+ * [0, total_items) and every user index inside [0, B), which is what keeps the
+ * kernels from faulting on bad offsets.  Host-only: touches no device.
+ */
+int64_t vista_summarize_schedule(const vista_summarize_desc* desc, const int64_t* offsets_host,
+                                 int64_t* tiles, int64_t max_tiles);
+
 /* Bytes of device workspace vista_summarize needs for this descriptor (0 if invalid).
  * The workspace must be 256-byte aligned.  Its first 4 bytes receive an int32
  * device-side status (0 = offsets passed the on-device check, VISTA_ERR_OFFSETS
@@ -112,6 +132,9 @@ size_t vista_summarize_workspace_bytes(const vista_summarize_desc* desc);
  *
  * Supported: bf16 with (d, H) = (128, 4) or (256, 8), S in {64, 128, 256, 512} (MFMA path);
  * any dtype with d/H <= 64, d <= 512, S <= 512 (plain fp32-ALU path).
+ * The workspace grows with the user count as well as with the history: the MFMA
+ * path keeps (G + B) partial records of H * S * 144 bytes (G = segments), the
+ * plain path the same count of H * S * (d/H + 2) * 4 bytes plus fp32 K and V.
  */
 vista_status vista_summarize(const vista_summarize_desc* desc,
                              const void* history_emb,

@@ -27,6 +27,7 @@ EXPORTS = (
     "vista_status_string",
     "vista_summarize_segment_items",
     "vista_summarize_workspace_bytes",
+    "vista_summarize_schedule",
     "vista_summarize",
     "vista_target_attend",
     "vista_sglu_ffn",
@@ -76,6 +77,8 @@ def lib() -> C.CDLL:
     L.vista_summarize_segment_items.argtypes = [C.POINTER(SummarizeDesc)]
     L.vista_summarize_workspace_bytes.restype = C.c_size_t
     L.vista_summarize_workspace_bytes.argtypes = [C.POINTER(SummarizeDesc)]
+    L.vista_summarize_schedule.restype = C.c_int64
+    L.vista_summarize_schedule.argtypes = [C.POINTER(SummarizeDesc), i64p, i64p, C.c_int64]
     L.vista_summarize.restype = C.c_int
     L.vista_summarize.argtypes = [C.POINTER(SummarizeDesc), vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
     L.vista_target_attend.restype = C.c_int
@@ -118,6 +121,22 @@ def vista_summarize_segment_items(desc: SummarizeDesc) -> int:
 
 def vista_summarize_workspace_bytes(desc: SummarizeDesc) -> int:
     return lib().vista_summarize_workspace_bytes(C.byref(desc))
+
+
+def vista_summarize_schedule(desc: SummarizeDesc, offsets_host):
+    """The tiles the kernels visit, int64 [n, 4] = (segment, user, first row, rows); host only.
+    ``offsets_host`` is a numpy int64 array of B + 1 entries (not validated by the call)."""
+    import numpy as np
+    off = np.ascontiguousarray(offsets_host, dtype=np.int64)
+    if off.size != desc.B + 1:
+        raise ValueError("offsets_host must hold B + 1 entries")
+    ptr = off.ctypes.data_as(C.POINTER(C.c_int64))
+    n = lib().vista_summarize_schedule(C.byref(desc), ptr, None, 0)
+    if n < 0:
+        raise VistaError(VISTA_ERR_SHAPE)
+    tiles = np.empty((n, 4), dtype=np.int64)
+    lib().vista_summarize_schedule(C.byref(desc), ptr, tiles.ctypes.data_as(C.POINTER(C.c_int64)), n)
+    return tiles
 
 
 def vista_summarize(history_emb, offsets, virtual_queries, W_k, W_v, out, *, H, scale=0.0,

@@ -384,9 +384,9 @@ __global__ __launch_bounds__(kThreads, (NKB <= 6 || NKB == 8) ? 3 : 2) void atte
 }
 
 template <int NKB>
-void launch(const AttendParams& p, hipStream_t s) {
+hipError_t launch_attend(const AttendParams& p, hipStream_t s) {
   const unsigned blocks = unsigned(p.B) * unsigned(p.H / kHeads) * unsigned(p.chunks);
-  hipLaunchKernelGGL(attend_mfma_kernel<NKB>, dim3(blocks), dim3(kThreads), 0, s, p);
+  return launch(attend_mfma_kernel<NKB>, dim3(blocks), dim3(kThreads), 0, s, p);
 }
 
 }  // namespace
@@ -416,23 +416,23 @@ vista_status mfma_target_attend(const vista_attend_desc& d, float scale_log2, co
   p.rounds_per_wg = per;
   p.chunks = (nrounds + per - 1) / per;
   if (groups * p.chunks > 0x7FFFFFFF) return VISTA_ERR_UNSUPPORTED;
+  hipError_t e;
   switch (nkb) {
-    case 1: launch<1>(p, s); break;
-    case 2: launch<2>(p, s); break;
-    case 3: launch<3>(p, s); break;
-    case 4: launch<4>(p, s); break;
-    case 5: launch<5>(p, s); break;
-    case 6: launch<6>(p, s); break;
-    case 7: launch<7>(p, s); break;
-    case 8: launch<8>(p, s); break;
-    case 10: launch<10>(p, s); break;
-    case 12: launch<12>(p, s); break;
-    case 14: launch<14>(p, s); break;
-    case 16: launch<16>(p, s); break;
+    case 1: e = launch_attend<1>(p, s); break;
+    case 2: e = launch_attend<2>(p, s); break;
+    case 3: e = launch_attend<3>(p, s); break;
+    case 4: e = launch_attend<4>(p, s); break;
+    case 5: e = launch_attend<5>(p, s); break;
+    case 6: e = launch_attend<6>(p, s); break;
+    case 7: e = launch_attend<7>(p, s); break;
+    case 8: e = launch_attend<8>(p, s); break;
+    case 10: e = launch_attend<10>(p, s); break;
+    case 12: e = launch_attend<12>(p, s); break;
+    case 14: e = launch_attend<14>(p, s); break;
+    case 16: e = launch_attend<16>(p, s); break;
     default: return VISTA_ERR_UNSUPPORTED;
   }
-  VISTA_LAUNCH_CHECK();
-  return VISTA_OK;
+  return e == hipSuccess ? VISTA_OK : VISTA_ERR_HIP;
 }
 
 }  // namespace vista

@@ -5,6 +5,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <tuple>
+#include <utility>
+
 #include "vista.h"
 
 namespace vista {
@@ -38,14 +41,19 @@ __host__ __device__ inline size_t plan_bytes(int64_t G) { return (size_t(G) * si
 // ---------------------------------------------------------------------------
 // offsets[] entries are read at workgroup-uniform addresses; telling the compiler
 // so keeps the whole piece walk (and everything derived from it) in scalar registers.
-__device__ __forceinline__ int64_t load_uniform(const int64_t* p) {
+// The walk is also compiled for the host (vista_summarize_schedule reports it).
+__host__ __device__ __forceinline__ int64_t load_uniform(const int64_t* p) {
   const int64_t v = *p;
+#if defined(__HIP_DEVICE_COMPILE__)
   const uint32_t lo = __builtin_amdgcn_readfirstlane(uint32_t(uint64_t(v)));
   const uint32_t hi = __builtin_amdgcn_readfirstlane(uint32_t(uint64_t(v) >> 32));
   return int64_t((uint64_t(hi) << 32) | lo);
+#else
+  return v;
+#endif
 }
 
-__device__ __forceinline__ int find_user(const int64_t* __restrict__ offsets, int B, int64_t row) {
+__host__ __device__ __forceinline__ int find_user(const int64_t* __restrict__ offsets, int B, int64_t row) {
   int lo = 0, hi = B;  // invariant: offsets[lo] <= row (offsets[0] = 0), answer in [lo, hi)
   while (hi - lo > 1) {
     int mid = (lo + hi) >> 1;
@@ -61,8 +69,8 @@ struct Piece {
 
 // Advances to the next piece of segment [pos, seg_end); returns false when done.
 // `user` and `pos` carry the walk state between calls.
-__device__ __forceinline__ bool next_piece(const int64_t* __restrict__ offsets, int B, int64_t seg_end,
-                                           int& user, int64_t& pos, Piece& out) {
+__host__ __device__ __forceinline__ bool next_piece(const int64_t* __restrict__ offsets, int B, int64_t seg_end,
+                                                    int& user, int64_t& pos, Piece& out) {
   while (pos < seg_end && user < B) {
     int64_t uend = load_uniform(offsets + user + 1);
     if (uend > pos) {
@@ -79,9 +87,75 @@ __device__ __forceinline__ bool next_piece(const int64_t* __restrict__ offsets, 
   return false;
 }
 
-#define VISTA_LAUNCH_CHECK()                                   \
-  do {                                                         \
-    if (hipGetLastError() != hipSuccess) return VISTA_ERR_HIP; \
+// A segment as one stream of tiles of `kTileItems` rows.  A tile never spans two
+// users: the cursor walks the pieces of the segment and cuts each into tiles, the
+// last of which may be ragged.  When the cursor runs off the segment it stays on
+// its last tile (still in bounds) with valid = false.  All state is scalar.
+constexpr int kTileItems = 32;
+struct TileCursor {
+  int wuser;        // piece walk: next user to look at
+  int64_t wpos;     // piece walk: next flat row (= end of the current piece)
+  int user;         // user of the current piece
+  int64_t row;      // first row of the current tile
+  int tiles_left;   // tiles of the current piece not yet passed, this one included
+  int tail;         // valid rows of the piece's last tile, 1..32
+  bool valid;
+
+  __host__ __device__ __forceinline__ void enter(const Piece& pc) {
+    const int64_t len = pc.end - pc.begin;            // 1 .. segment size: fits 32 bits
+    user = pc.user;
+    row = pc.begin;
+    tiles_left = int((len + kTileItems - 1) / kTileItems);
+    tail = int(len - int64_t(tiles_left - 1) * kTileItems);
+  }
+  // first_user: the user owning row seg_begin (last user whose first row is <= seg_begin)
+  __host__ __device__ __forceinline__ void init(const int64_t* __restrict__ offsets, int B, int first_user,
+                                                int64_t seg_begin, int64_t seg_end) {
+    wuser = first_user;
+    wpos = seg_begin;
+    Piece pc;
+    pc.user = 0;
+    pc.begin = seg_begin;
+    pc.end = seg_begin + 1;          // overwritten unless offsets are invalid; stays inside [0, N)
+    valid = next_piece(offsets, B, seg_end, wuser, wpos, pc);
+    enter(pc);
+  }
+  __host__ __device__ __forceinline__ void advance(const int64_t* __restrict__ offsets, int B, int64_t seg_end) {
+    if (!valid) return;
+    if (tiles_left > 1) {
+      --tiles_left;
+      row += kTileItems;
+    } else {
+      Piece nx;
+      if (next_piece(offsets, B, seg_end, wuser, wpos, nx))
+        enter(nx);
+      else
+        valid = false;               // stays on its last tile
+    }
+  }
+  // valid rows of the current tile
+  __host__ __device__ __forceinline__ int rows() const { return tiles_left == 1 ? tail : kTileItems; }
+};
+
+template <typename Tuple, size_t... I>
+inline void fill_arg_pointers(void** ptrs, Tuple& vals, std::index_sequence<I...>) {
+  ((ptrs[I] = static_cast<void*>(&std::get<I>(vals))), ...);
+}
+
+// Launches a kernel and reports this launch's own status (an error left behind by an
+// earlier, unrelated call of the application is neither reported nor cleared).
+template <typename... KArgs, typename... Args>
+inline hipError_t launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds, hipStream_t stream,
+                         Args... args) {
+  std::tuple<KArgs...> vals{static_cast<KArgs>(args)...};
+  void* ptrs[sizeof...(KArgs) > 0 ? sizeof...(KArgs) : 1];
+  fill_arg_pointers(ptrs, vals, std::index_sequence_for<KArgs...>{});
+  return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, ptrs, lds, stream);
+}
+
+#define VISTA_LAUNCH(...)                                              \
+  do {                                                                 \
+    if (::vista::launch(__VA_ARGS__) != hipSuccess) return VISTA_ERR_HIP; \
   } while (0)
 
 // Launchers implemented in the kernel files (host side).
@@ -122,7 +196,7 @@ vista_status mfma_sglu_ffn(const vista_ffn_desc& d, float eps, const void* y, co
 // Validates offsets on the device (status word) and records, for every segment,
 // the user that owns its first row (seg_user[g], int32), so that the main
 // kernels start their piece walk without a search.
-void launch_plan(const int64_t* offsets, int B, int64_t N, int seg, int64_t G, int* status, int* seg_user,
-                 hipStream_t s);
+hipError_t launch_plan(const int64_t* offsets, int B, int64_t N, int seg, int64_t G, int* status, int* seg_user,
+                       hipStream_t s);
 
 }  // namespace vista

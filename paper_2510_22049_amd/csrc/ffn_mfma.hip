@@ -277,10 +277,9 @@ vista_status mfma_sglu_ffn(const vista_ffn_desc& d, float eps, const void* y, co
   p.eps = eps;
   const unsigned blocks = unsigned((int64_t(d.rows) + kFfnRows - 1) / kFfnRows);
   if (d.d == 128)
-    hipLaunchKernelGGL(ffn_mfma_kernel<128>, dim3(blocks), dim3(64 * kFfnWaves), 0, s, p);
+    VISTA_LAUNCH(ffn_mfma_kernel<128>, dim3(blocks), dim3(64 * kFfnWaves), 0, s, p);
   else
-    hipLaunchKernelGGL(ffn_mfma_kernel<256>, dim3(blocks), dim3(64 * kFfnWaves), 0, s, p);
-  VISTA_LAUNCH_CHECK();
+    VISTA_LAUNCH(ffn_mfma_kernel<256>, dim3(blocks), dim3(64 * kFfnWaves), 0, s, p);
   return VISTA_OK;
 }
 

@@ -41,12 +41,12 @@ __global__ void plan_kernel(const int64_t* __restrict__ offsets, int B, int64_t 
   }
 }
 
-void launch_plan(const int64_t* offsets, int B, int64_t N, int seg, int64_t G, int* status, int* seg_user,
-                 hipStream_t s) {
+hipError_t launch_plan(const int64_t* offsets, int B, int64_t N, int seg, int64_t G, int* status, int* seg_user,
+                       hipStream_t s) {
   int blocks = int((G + 255) / 256);
   if (blocks < 1) blocks = 1;
   if (blocks > 1024) blocks = 1024;
-  hipLaunchKernelGGL(plan_kernel, dim3(blocks), dim3(256), 0, s, offsets, B, N, seg, G, status, seg_user);
+  return launch(plan_kernel, dim3(blocks), dim3(256), 0, s, offsets, B, N, seg, G, status, seg_user);
 }
 
 // -------------------------------------------------- stage 1: K/V projection
@@ -181,18 +181,15 @@ static vista_status generic_summarize_t(const SummarizeArgs& a) {
     int64_t total = N * d.d;
     int64_t blocks = (total + 255) / 256;
     if (blocks > 0x7FFFFFFF) return VISTA_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(project_kernel<T>, dim3(unsigned(blocks)), dim3(256), 0, a.stream,
+    VISTA_LAUNCH(project_kernel<T>, dim3(unsigned(blocks)), dim3(256), 0, a.stream,
                        static_cast<const T*>(a.X), static_cast<const T*>(a.Wk), static_cast<const T*>(a.Wv),
                        K, V, N, d.d);
-    VISTA_LAUNCH_CHECK();
-    hipLaunchKernelGGL(attend_history_kernel<T>, dim3(unsigned(a.G), d.H), dim3(64), 0, a.stream, K, V,
+    VISTA_LAUNCH(attend_history_kernel<T>, dim3(unsigned(a.G), d.H), dim3(64), 0, a.stream, K, V,
                        static_cast<const T*>(a.Q), d.q_user_stride, a.offsets, d.B, d.S, d.d, d.H,
                        a.scale_log2, N, a.seg, a.seg_user, partials);
-    VISTA_LAUNCH_CHECK();
   }
-  hipLaunchKernelGGL(merge_kernel<T>, dim3(d.B, d.H), dim3(256), 0, a.stream, partials, a.offsets, d.S, d.d,
+  VISTA_LAUNCH(merge_kernel<T>, dim3(d.B, d.H), dim3(256), 0, a.stream, partials, a.offsets, d.S, d.d,
                      d.H, a.seg, a.G, static_cast<T*>(a.out));
-  VISTA_LAUNCH_CHECK();
   return VISTA_OK;
 }
 
@@ -247,14 +244,13 @@ vista_status generic_target_attend(const vista_attend_desc& d, float scale_log2,
   int64_t blocks = (total + 127) / 128;
   if (blocks > 0x7FFFFFFF) return VISTA_ERR_UNSUPPORTED;
   if (d.dtype == VISTA_BF16)
-    hipLaunchKernelGGL(target_attend_kernel<bf16_t>, dim3(unsigned(blocks)), dim3(128), 0, s,
+    VISTA_LAUNCH(target_attend_kernel<bf16_t>, dim3(unsigned(blocks)), dim3(128), 0, s,
                        static_cast<const bf16_t*>(cand), static_cast<const bf16_t*>(summ),
                        static_cast<bf16_t*>(out), total, d.C, d.S, d.d, d.H, scale_log2);
   else
-    hipLaunchKernelGGL(target_attend_kernel<float>, dim3(unsigned(blocks)), dim3(128), 0, s,
+    VISTA_LAUNCH(target_attend_kernel<float>, dim3(unsigned(blocks)), dim3(128), 0, s,
                        static_cast<const float*>(cand), static_cast<const float*>(summ),
                        static_cast<float*>(out), total, d.C, d.S, d.d, d.H, scale_log2);
-  VISTA_LAUNCH_CHECK();
   return VISTA_OK;
 }
 
@@ -315,16 +311,15 @@ vista_status generic_sglu_ffn(const vista_ffn_desc& d, float eps, const void* y,
   if (blocks > 0x7FFFFFFF) return VISTA_ERR_UNSUPPORTED;
   size_t lds = size_t(kFfnRows) * (d.d + d.d_ff) * sizeof(float);
   if (d.dtype == VISTA_BF16)
-    hipLaunchKernelGGL(sglu_ffn_kernel<bf16_t>, dim3(unsigned(blocks)), dim3(256), lds, s,
+    VISTA_LAUNCH(sglu_ffn_kernel<bf16_t>, dim3(unsigned(blocks)), dim3(256), lds, s,
                        static_cast<const bf16_t*>(y), static_cast<const bf16_t*>(Wg),
                        static_cast<const bf16_t*>(Wu), static_cast<const bf16_t*>(Wo),
                        static_cast<bf16_t*>(out), d.rows, d.d, d.d_ff, eps);
   else
-    hipLaunchKernelGGL(sglu_ffn_kernel<float>, dim3(unsigned(blocks)), dim3(256), lds, s,
+    VISTA_LAUNCH(sglu_ffn_kernel<float>, dim3(unsigned(blocks)), dim3(256), lds, s,
                        static_cast<const float*>(y), static_cast<const float*>(Wg),
                        static_cast<const float*>(Wu), static_cast<const float*>(Wo),
                        static_cast<float*>(out), d.rows, d.d, d.d_ff, eps);
-  VISTA_LAUNCH_CHECK();
   return VISTA_OK;
 }
 

@@ -37,7 +37,7 @@ typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 
-constexpr int kTile = 32;            // items per tile
+constexpr int kTile = kTileItems;    // items per tile
 constexpr float kSafeBound2 = 3600.f;  // (60)^2: |q|^2 |k|^2 below this keeps 2^s in range
 constexpr int kRecRows = 18;         // 16 O registers + l + m per lane
 constexpr int kRecFloats = kRecRows * 64;
@@ -229,50 +229,15 @@ __device__ __forceinline__ void summarize_wave(const MfmaSummarizeParams& p, Sum
   };
   if (p.q_user_stride == 0) load_queries(0);
 
-  // ---- the segment as one stream of tiles.  A tile never spans two users; a
-  // cursor walks the pieces of the segment (scalar state, offsets read through
-  // uniform loads).  `ca` names the tile being attended over, `cf` runs three
-  // tiles ahead and names the tile whose rows are requested from HBM.  When a
-  // cursor runs off the segment it stays on its last tile (still in bounds).
-  struct Cursor {
-    int wuser;        // piece walk: next user to look at
-    int64_t wpos;     // piece walk: next flat row (= end of the current piece)
-    int user;         // user of the current piece
-    int64_t row;      // first row of the current tile
-    int tiles_left;   // tiles of the current piece not yet passed, this one included
-    int tail;         // valid rows of the piece's last tile, 1..32
-    bool valid;
-  };
-  auto cursor_enter = [&](Cursor& c, const Piece& pc) __attribute__((always_inline)) {
-    const int64_t len = pc.end - pc.begin;            // 1 .. segment size: fits 32 bits
-    c.user = pc.user;
-    c.row = pc.begin;
-    c.tiles_left = int((len + kTile - 1) / kTile);
-    c.tail = int(len - int64_t(c.tiles_left - 1) * kTile);
-  };
+  // ---- the segment as one stream of tiles (TileCursor: scalar state, offsets read through
+  // uniform loads).  `ca` names the tile being attended over, `cf` runs three tiles ahead
+  // and names the tile whose rows are requested from HBM.
+  using Cursor = TileCursor;
   auto cursor_init = [&](Cursor& c) __attribute__((always_inline)) {
-    c.wuser = p.seg_user ? __builtin_amdgcn_readfirstlane(p.seg_user[g]) : find_user(p.offsets, p.B, seg_begin);
-    c.wpos = seg_begin;
-    Piece pc;
-    pc.user = 0;
-    pc.begin = seg_begin;
-    pc.end = seg_begin + 1;          // overwritten unless offsets are invalid; stays inside [0, N)
-    c.valid = next_piece(p.offsets, p.B, seg_end, c.wuser, c.wpos, pc);
-    cursor_enter(c, pc);
+    const int first = p.seg_user ? __builtin_amdgcn_readfirstlane(p.seg_user[g]) : find_user(p.offsets, p.B, seg_begin);
+    c.init(p.offsets, p.B, first, seg_begin, seg_end);
   };
-  auto cursor_advance = [&](Cursor& c) __attribute__((always_inline)) {
-    if (!c.valid) return;
-    if (c.tiles_left > 1) {
-      --c.tiles_left;
-      c.row += kTile;
-    } else {
-      Piece nx;
-      if (next_piece(p.offsets, p.B, seg_end, c.wuser, c.wpos, nx))
-        cursor_enter(c, nx);
-      else
-        c.valid = false;             // stays on its last tile
-    }
-  };
+  auto cursor_advance = [&](Cursor& c) __attribute__((always_inline)) { c.advance(p.offsets, p.B, seg_end); };
 
   f32x16 o[NQB];
   float l[NQB], m[NQB];
@@ -569,13 +534,14 @@ __global__ __launch_bounds__(512) void summarize_mfma4_kernel(MfmaSummarizeParam
 
 // Merge of a user's partial records, ascending segment order (fixed, so the
 // result is bitwise reproducible): with m the running maximum of the m_c,
-// out = sum_c 2^(m_c - m) O_c / sum_c 2^(m_c - m) l_c.   grid (S/32, H, B), 256 threads: wave w
+// out = sum_c 2^(m_c - m) O_c / sum_c 2^(m_c - m) l_c.   One block per (user, head, query block), 256 threads: wave w
 // owns accumulator registers 4w..4w+3, i.e. channels 8w + 4 hf + 0..3.
 __global__ __launch_bounds__(256) void merge_mfma_kernel(const float* __restrict__ partials,
                                                          const int64_t* __restrict__ offsets, int S, int d,
                                                          int H, int seg, int64_t G,
                                                          uint16_t* __restrict__ out, int* status) {
-  const int qb = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int nqb = S / 32;
+  const int qb = blockIdx.x % nqb, h = (blockIdx.x / nqb) % H, b = blockIdx.x / (nqb * H);
   // without a plan kernel in front (offsets checked on the host) the status word is cleared here
   if (status && qb == 0 && h == 0 && b == 0 && threadIdx.x == 0) *status = VISTA_OK;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -589,7 +555,6 @@ __global__ __launch_bounds__(256) void merge_mfma_kernel(const float* __restrict
   int64_t g0 = begin / seg, g1 = (end - 1) / seg;
   if (g0 < 0) g0 = 0;
   if (g1 > G - 1) g1 = G - 1;
-  const int nqb = S / 32;
   auto rec = [&](int64_t g) __attribute__((always_inline)) { return partials + (((g + b) * H + h) * nqb + qb) * kRecFloats + lane; };
   // One pass with a running maximum (rescale when it moves); loads are issued kBatch
   // records at a time so a long user is not a chain of dependent round trips.
@@ -650,17 +615,17 @@ size_t mfma_summarize_workspace(const vista_summarize_desc& d, int seg) {
 }
 
 template <int D, int NQB>
-static void launch_main4(const MfmaSummarizeParams& p, int64_t G, hipStream_t s) {
+static hipError_t launch_main4(const MfmaSummarizeParams& p, int64_t G, hipStream_t s) {
   const int64_t groups = (G + 7) / 8;
   const int64_t blocks = groups * 8 * p.nhg;
-  hipLaunchKernelGGL((summarize_mfma4_kernel<D, NQB>), dim3(unsigned(blocks)), dim3(512), 0, s, p);
+  return launch(summarize_mfma4_kernel<D, NQB>, dim3(unsigned(blocks)), dim3(512), 0, s, p);
 }
 
 template <int D, int NQB, int HPW>
-static void launch_main(const MfmaSummarizeParams& p, int64_t G, hipStream_t s) {
+static hipError_t launch_main(const MfmaSummarizeParams& p, int64_t G, hipStream_t s) {
   const int64_t groups = (G + 7) / 8;
   const int64_t blocks = groups * 8 * p.nhg;
-  hipLaunchKernelGGL((summarize_mfma_kernel<D, NQB, HPW>), dim3(unsigned(blocks)), dim3(HPW * 128), 0, s, p);
+  return launch(summarize_mfma_kernel<D, NQB, HPW>, dim3(unsigned(blocks)), dim3(HPW * 128), 0, s, p);
 }
 
 vista_status mfma_summarize(const SummarizeArgs& a) {
@@ -681,36 +646,35 @@ vista_status mfma_summarize(const SummarizeArgs& a) {
   p.N = d.total_items;
   p.seg = a.seg;
   p.c = a.scale_log2;
+  const int64_t merge_blocks = int64_t(d.B) * d.H * (d.S / 32);
+  if ((a.G + 7) / 8 * 8 * 4 > 0x7FFFFFFF || merge_blocks > 0x7FFFFFFF) return VISTA_ERR_UNSUPPORTED;
   if (a.G > 0) {
-    if ((a.G + 7) / 8 * 8 * 4 > 0x7FFFFFFF) return VISTA_ERR_UNSUPPORTED;
+    hipError_t e;
     if (shape_d128(d)) {
       p.nhg = 1;
       switch (d.S) {
-        case 64: launch_main<128, 1, 4>(p, a.G, a.stream); break;
-        case 128: launch_main<128, 2, 4>(p, a.G, a.stream); break;
-        case 256:
-          launch_main<128, 4, 4>(p, a.G, a.stream);
-          break;
+        case 64: e = launch_main<128, 1, 4>(p, a.G, a.stream); break;
+        case 128: e = launch_main<128, 2, 4>(p, a.G, a.stream); break;
+        case 256: e = launch_main<128, 4, 4>(p, a.G, a.stream); break;
         default:
           p.nhg = 2;
-          launch_main4<128, 4>(p, a.G, a.stream);
+          e = launch_main4<128, 4>(p, a.G, a.stream);
           break;
       }
     } else {
       p.nhg = 4;
       switch (d.S) {
-        case 64: launch_main<256, 1, 2>(p, a.G, a.stream); break;
-        case 128: launch_main4<256, 1>(p, a.G, a.stream); break;
-        case 256: launch_main4<256, 2>(p, a.G, a.stream); break;
-        default: launch_main4<256, 4>(p, a.G, a.stream); break;
+        case 64: e = launch_main<256, 1, 2>(p, a.G, a.stream); break;
+        case 128: e = launch_main4<256, 1>(p, a.G, a.stream); break;
+        case 256: e = launch_main4<256, 2>(p, a.G, a.stream); break;
+        default: e = launch_main4<256, 4>(p, a.G, a.stream); break;
       }
     }
-    VISTA_LAUNCH_CHECK();
+    if (e != hipSuccess) return VISTA_ERR_HIP;
   }
-  hipLaunchKernelGGL(merge_mfma_kernel, dim3(d.S / 32, d.H, d.B), dim3(256), 0, a.stream, p.partials, a.offsets,
-                     d.S, d.d, d.H, a.seg, a.G, static_cast<uint16_t*>(a.out),
-                     a.seg_user ? nullptr : reinterpret_cast<int*>(a.workspace));
-  VISTA_LAUNCH_CHECK();
+  VISTA_LAUNCH(merge_mfma_kernel, dim3(unsigned(merge_blocks)), dim3(256), 0, a.stream, p.partials, a.offsets, d.S,
+               d.d, d.H, a.seg, a.G, static_cast<uint16_t*>(a.out),
+               a.seg_user ? nullptr : reinterpret_cast<int*>(a.workspace));
   return VISTA_OK;
 }
 

@@ -59,6 +59,34 @@ int32_t vista_summarize_segment_items(const vista_summarize_desc* desc) {
   return resolve_segment(desc);
 }
 
+int64_t vista_summarize_schedule(const vista_summarize_desc* desc, const int64_t* offsets_host, int64_t* tiles,
+                                 int64_t max_tiles) {
+  if (check_summarize_desc(desc) != VISTA_OK || !offsets_host || max_tiles < 0 || (max_tiles > 0 && !tiles))
+    return -1;
+  const int seg = resolve_segment(desc);
+  const int64_t N = desc->total_items;
+  const int64_t G = (N + seg - 1) / seg;
+  int64_t n = 0;
+  for (int64_t g = 0; g < G; ++g) {
+    const int64_t seg_begin = g * seg;
+    const int64_t seg_end = seg_begin + seg < N ? seg_begin + seg : N;
+    TileCursor c;
+    c.init(offsets_host, desc->B, find_user(offsets_host, desc->B, seg_begin), seg_begin, seg_end);
+    while (c.valid) {
+      if (n < max_tiles) {
+        int64_t* t = tiles + 4 * n;
+        t[0] = g;
+        t[1] = c.user;
+        t[2] = c.row;
+        t[3] = c.rows();
+      }
+      ++n;
+      c.advance(offsets_host, desc->B, seg_end);
+    }
+  }
+  return n;
+}
+
 size_t vista_summarize_workspace_bytes(const vista_summarize_desc* desc) {
   if (check_summarize_desc(desc) != VISTA_OK) return 0;
   int seg = resolve_segment(desc);
@@ -107,8 +135,9 @@ vista_status vista_summarize(const vista_summarize_desc* desc, const void* histo
   }
   int* seg_user = reinterpret_cast<int*>(a.workspace + kHeaderBytes);
   a.seg_user = seg_user;
-  launch_plan(offsets, desc->B, desc->total_items, a.seg, a.G, reinterpret_cast<int*>(workspace), seg_user, a.stream);
-  if (hipGetLastError() != hipSuccess) return VISTA_ERR_HIP;
+  if (launch_plan(offsets, desc->B, desc->total_items, a.seg, a.G, reinterpret_cast<int*>(workspace), seg_user,
+                  a.stream) != hipSuccess)
+    return VISTA_ERR_HIP;
   return mfma_summarize_supported(*desc) ? mfma_summarize(a) : generic_summarize(a);
 }
 
