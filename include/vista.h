@@ -42,7 +42,8 @@ typedef enum {
   VISTA_ERR_OFFSETS = 3,     /* offsets_host: not starting at 0, decreasing, or not ending at total_items */
   VISTA_ERR_UNSUPPORTED = 4, /* dtype / head width / S outside the supported set */
   VISTA_ERR_WORKSPACE = 5,   /* workspace pointer NULL, misaligned or too small */
-  VISTA_ERR_HIP = 6          /* the runtime refused a kernel launch of this call */
+  VISTA_ERR_HIP = 6,         /* the runtime refused a kernel launch of this call */
+  VISTA_ERR_SCRATCH = 7      /* vista_summarize_static: the call needs more than VISTA_STATIC_SCRATCH_BYTES */
 } vista_status;
 
 /* storage dtype of every tensor of a call; accumulation is always fp32 */
@@ -146,6 +147,36 @@ vista_status vista_summarize(const vista_summarize_desc* desc,
                              void* out,
                              void* workspace, size_t workspace_bytes,
                              void* hip_stream);
+
+/*
+ * vista_summarize for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same computation, same kernels, same results bit for bit as
+ * vista_summarize with the same descriptor; the workspace is a static device
+ * array of VISTA_STATIC_SCRATCH_BYTES inside the library (one per GPU the
+ * library runs on, held until the process ends).  The call allocates nothing.
+ *
+ *   - A descriptor whose vista_summarize_workspace_bytes exceeds
+ *     VISTA_STATIC_SCRATCH_BYTES is rejected with VISTA_ERR_SCRATCH before any
+ *     launch (64 MiB holds the 64-user, 0.77 M-item, S = 256, d = 128 batch with
+ *     a third to spare).
+ *   - The first call on a device looks up that device's copy of the array
+ *     (no allocation, but make it outside a graph capture).
+ *   - All calls on one GPU share that GPU's array: calls that may overlap on one
+ *     GPU (different streams, no ordering between them) race; order them.
+ *   - The device-side offsets status (offsets_host == NULL) stays inside the
+ *     library; pass offsets_host to have the offsets checked.
+ */
+#define VISTA_STATIC_SCRATCH_BYTES (64u << 20)
+vista_status vista_summarize_static(const vista_summarize_desc* desc,
+                                    const void* history_emb,
+                                    const int64_t* offsets,
+                                    const int64_t* offsets_host,
+                                    const void* virtual_queries,
+                                    const void* W_k,
+                                    const void* W_v,
+                                    void* out,
+                                    void* hip_stream);
 
 /* ---------------------------------------------------------------- stage 2 */
 

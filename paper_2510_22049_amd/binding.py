@@ -19,7 +19,8 @@ LIB_PATH = os.path.join(_HERE, "libvista.so")
 
 VISTA_OK = 0
 VISTA_ERR_NULL, VISTA_ERR_SHAPE, VISTA_ERR_OFFSETS = 1, 2, 3
-VISTA_ERR_UNSUPPORTED, VISTA_ERR_WORKSPACE, VISTA_ERR_HIP = 4, 5, 6
+VISTA_ERR_UNSUPPORTED, VISTA_ERR_WORKSPACE, VISTA_ERR_HIP, VISTA_ERR_SCRATCH = 4, 5, 6, 7
+VISTA_STATIC_SCRATCH_BYTES = 64 << 20
 VISTA_F32, VISTA_BF16 = 0, 1
 VISTA_ATTN_SOFTMAX = 0
 
@@ -29,6 +30,7 @@ EXPORTS = (
     "vista_summarize_workspace_bytes",
     "vista_summarize_schedule",
     "vista_summarize",
+    "vista_summarize_static",
     "vista_target_attend",
     "vista_sglu_ffn",
 )
@@ -81,6 +83,8 @@ def lib() -> C.CDLL:
     L.vista_summarize_schedule.argtypes = [C.POINTER(SummarizeDesc), i64p, i64p, C.c_int64]
     L.vista_summarize.restype = C.c_int
     L.vista_summarize.argtypes = [C.POINTER(SummarizeDesc), vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+    L.vista_summarize_static.restype = C.c_int
+    L.vista_summarize_static.argtypes = [C.POINTER(SummarizeDesc), vp, vp, vp, vp, vp, vp, vp, vp]
     L.vista_target_attend.restype = C.c_int
     L.vista_target_attend.argtypes = [C.POINTER(AttendDesc), vp, vp, vp, vp]
     L.vista_sglu_ffn.restype = C.c_int
@@ -166,6 +170,28 @@ def vista_summarize(history_emb, offsets, virtual_queries, W_k, W_v, out, *, H, 
     if st != VISTA_OK:
         raise VistaError(st)
     return workspace
+
+
+def vista_summarize_static(history_emb, offsets, virtual_queries, W_k, W_v, out, *, H, scale=0.0,
+                           segment_items=0, offsets_host=None):
+    """Stage 1 on the library's static scratch: no workspace argument, nothing allocated."""
+    B = offsets.numel() - 1
+    S, d = virtual_queries.shape[-2:]
+    N = history_emb.shape[0]
+    desc = summarize_desc(B, S, d, H, _dtype_code(history_emb), N, virtual_queries.dim() == 3, scale,
+                          segment_items)
+    host = None
+    if offsets_host is not None:
+        if offsets_host.is_cuda or offsets_host.dtype != torch.int64:
+            raise ValueError("offsets_host must be a CPU int64 tensor")
+        host = offsets_host.contiguous().data_ptr()
+    if offsets.dtype != torch.int64:
+        raise TypeError("offsets must be int64")
+    st = lib().vista_summarize_static(C.byref(desc), _dev(history_emb, "history_emb") if N else None,
+                                      _dev(offsets, "offsets"), host, _dev(virtual_queries, "virtual_queries"),
+                                      _dev(W_k, "W_k"), _dev(W_v, "W_v"), _dev(out, "out"), _stream())
+    if st != VISTA_OK:
+        raise VistaError(st)
 
 
 def vista_target_attend(candidates, summaries, out, *, H, scale=0.0):

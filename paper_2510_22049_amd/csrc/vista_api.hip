@@ -2,6 +2,8 @@
 // the kernel families.  No allocation, no synchronisation, no global state.
 #include <math.h>
 
+#include <mutex>
+
 #include "common.hpp"
 
 using namespace vista;
@@ -37,6 +39,28 @@ int32_t resolve_segment(const vista_summarize_desc* d) {
   return int32_t(s);
 }
 
+// Scratch of vista_summarize_static: one array per GPU the library runs on, held until the
+// process ends.  In host code the name below only stands for the symbol; the array's device
+// address is looked up once per device and kept in static_scratch_ptr.
+static __device__ __align__(256) unsigned char scratch[VISTA_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+void* static_scratch_ptr[kMaxDevices] = {};
+std::mutex static_scratch_mutex;
+
+// Device address of the current device's scratch array (nullptr on failure).
+void* static_scratch() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(static_scratch_mutex);
+  if (!static_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+    static_scratch_ptr[dev] = ptr;
+  }
+  return static_scratch_ptr[dev];
+}
+
 }  // namespace
 
 extern "C" {
@@ -50,6 +74,8 @@ const char* vista_status_string(int status) {
     case VISTA_ERR_UNSUPPORTED: return "VISTA_ERR_UNSUPPORTED: dtype, head width or S outside the supported set";
     case VISTA_ERR_WORKSPACE: return "VISTA_ERR_WORKSPACE: workspace NULL, misaligned or too small";
     case VISTA_ERR_HIP: return "VISTA_ERR_HIP: a kernel launch failed";
+    case VISTA_ERR_SCRATCH:
+      return "VISTA_ERR_SCRATCH: the call needs more than the library's static scratch (VISTA_STATIC_SCRATCH_BYTES)";
     default: return "unknown vista status";
   }
 }
@@ -139,6 +165,22 @@ vista_status vista_summarize(const vista_summarize_desc* desc, const void* histo
                   a.stream) != hipSuccess)
     return VISTA_ERR_HIP;
   return mfma_summarize_supported(*desc) ? mfma_summarize(a) : generic_summarize(a);
+}
+
+vista_status vista_summarize_static(const vista_summarize_desc* desc, const void* history_emb,
+                                    const int64_t* offsets, const int64_t* offsets_host,
+                                    const void* virtual_queries, const void* W_k, const void* W_v, void* out,
+                                    void* hip_stream) {
+  vista_status st = check_summarize_desc(desc);
+  if (st != VISTA_OK) return st;
+  const size_t need = vista_summarize_workspace_bytes(desc);
+  if (need > size_t(VISTA_STATIC_SCRATCH_BYTES)) return VISTA_ERR_SCRATCH;
+  void* ws = static_scratch();
+  if (!ws) return VISTA_ERR_HIP;
+  // Nothing in the scratch has to start at zero: every record the merge reads and the status
+  // word are written by this call's own kernels before they are read.
+  return vista_summarize(desc, history_emb, offsets, offsets_host, virtual_queries, W_k, W_v, out, ws,
+                         size_t(VISTA_STATIC_SCRATCH_BYTES), hip_stream);
 }
 
 vista_status vista_target_attend(const vista_attend_desc* desc, const void* candidates,
