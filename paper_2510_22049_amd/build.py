@@ -3,7 +3,9 @@
     python -m paper_2510_22049_amd.build
 
 Every translation unit under csrc/ is compiled to an object (in parallel) and
-linked into paper_2510_22049_amd/libvista.so, the one library the binding loads.
+linked into paper_2510_22049_amd/libvista.so, the one library the binding loads;
+calibrate.hip (the benchmark's calibration kernels, not on the product path)
+becomes libvista_calibrate.so, a library of its own.
 """
 from __future__ import annotations
 
@@ -17,6 +19,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libvista.so")
+CAL_LIB = os.path.join(HERE, "libvista_calibrate.so")
+CAL_SRC = "calibrate.hip"
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 # Packed-fp32 instructions are switched off for all device code on the test machines.
@@ -50,12 +54,15 @@ def build(verbose: bool = True) -> str:
     os.makedirs(OBJ, exist_ok=True)
     with ThreadPoolExecutor(max_workers=min(8, len(sources()))) as ex:
         objs = list(ex.map(_compile, sources()))
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB]
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("link failed:\n" + r.stderr)
-    if verbose:
-        print(f"built {LIB} from {len(objs)} sources")
+    srcs = sources()
+    for lib, group in ((LIB, [o for o, f in zip(objs, srcs) if f != CAL_SRC]),
+                       (CAL_LIB, [o for o, f in zip(objs, srcs) if f == CAL_SRC])):
+        cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *group, "-o", lib]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("link failed:\n" + r.stderr)
+        if verbose:
+            print(f"built {lib} from {len(group)} sources")
     return LIB
 
 

@@ -34,6 +34,8 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) short i16x4;
 
 namespace {
 
@@ -258,6 +260,9 @@ __global__ __launch_bounds__(kThreads, (NKB <= 6 || NKB == 8) ? 3 : 2) void atte
 
   // operand position of this lane inside its part: row l32, chunk 2 ks + hf
   const int osw = (l32 >> 2) & 3;
+  // A operand of the denominator products: ones in row 0 of every 4x4 block
+  const uint32_t onesw = (lane & 3) == 0 ? 0x3F803F80u : 0u;
+  const uint2 onesrow = make_uint2(onesw, onesw);
   lds_barrier();                                 // the V operands of all key blocks are in place
 
   // Round r lives in buffer (r - r0) mod NB.  Its part was requested NB-1 rounds ago; loads
@@ -294,10 +299,11 @@ __global__ __launch_bounds__(kThreads, (NKB <= 6 || NKB == 8) ? 3 : 2) void atte
     f32x16 o = {0};
     float lsum;
     if (!general) {
-      // The denominator adds the weights before their rounding to bf16: plain adds run beside
-      // the matrix core (the packed dot product does not, and taking the sums with an all-ones
-      // MFMA operand measured 3 % slower than the adds).
-      float l[4] = {0.f, 0.f, 0.f, 0.f};
+      // The denominator on the matrix core: a 4x4x4 product (16 blocks, one per four lanes) whose
+      // A block has ones in its first row adds a lane's own four packed weights into register 0
+      // of that lane.  It issues like one plain vector instruction for four weights (a chain of
+      // adds takes four) and sums the bf16 weights the numerator uses; two accumulators take turns.
+      f32x4 lacc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
       f32x16 nx = {0};
       nx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[0][0], c0.v, nx, 0, 0, 0);
       nx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[0][1], c1.v, nx, 0, 0, 0);
@@ -315,15 +321,20 @@ __global__ __launch_bounds__(kThreads, (NKB <= 6 || NKB == 8) ? 3 : 2) void atte
         Pack8 p0, p1;
 #pragma unroll
         for (int i = 0; i < 16; i += 2) {
-          const float ea = __builtin_amdgcn_exp2f(sc[i]), eb = __builtin_amdgcn_exp2f(sc[i + 1]);
-          const uint32_t pk = cvt_pk_bf16(ea, eb);
-          l[(i / 2) & 3] += ea + eb;
+          const uint32_t pk = cvt_pk_bf16(__builtin_amdgcn_exp2f(sc[i]), __builtin_amdgcn_exp2f(sc[i + 1]));
           if (i < 8) p0.w[i / 2] = pk; else p1.w[(i - 8) / 2] = pk;
+        }
+#pragma unroll
+        for (int part = 0; part < 4; ++part) {
+          const uint2 pw = part < 2 ? make_uint2(p0.w[2 * part], p0.w[2 * part + 1])
+                                    : make_uint2(p1.w[2 * part - 4], p1.w[2 * part - 3]);
+          lacc[part & 1] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(i16x4, onesrow),
+                                                                  __builtin_bit_cast(i16x4, pw), lacc[part & 1], 0, 0, 0);
         }
         o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v0.v, p0.v, o, 0, 0, 0);
         o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v1.v, p1.v, o, 0, 0, 0);
       }
-      lsum = (l[0] + l[1]) + (l[2] + l[3]);
+      lsum = lacc[0][0] + lacc[1][0];
       lsum += __shfl_xor(lsum, 32, 64);
     } else {
       float l[4] = {0.f, 0.f, 0.f, 0.f};

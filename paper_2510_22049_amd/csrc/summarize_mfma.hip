@@ -36,6 +36,8 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) short i16x4;
 
 constexpr int kTile = kTileItems;    // items per tile
 constexpr float kSafeBound2 = 3600.f;  // (60)^2: |q|^2 |k|^2 below this keeps 2^s in range
@@ -140,14 +142,14 @@ __device__ __forceinline__ void attend_block(const bf16x8& kop0, const bf16x8& k
 template <int V>
 struct Int { static constexpr int value = V; };
 
-constexpr int kXBuf = 3;             // X tiles in LDS: one being projected, two on their way
+constexpr int kXBuf = 3;             // ring depth of the X tiles and of the projected tiles in LDS
 
 // Shared memory of one workgroup.
 template <int D, int HPW>
 struct SummarizeLds {
   uint4 xbuf[kXBuf][(D / 8) * 32];    // X tiles: [16-byte chunk][item], filled by direct global->LDS loads
-  uint4 kvbuf[2][HPW][2][2][64];      // [buffer][head][K|V][half of the 16 registers][lane]
-  float knorm[2][HPW][64];            // squared norm of the scaled key rows (half per lane)
+  uint4 kvbuf[kXBuf][HPW][2][2][64];  // projected tiles: [ring slot][head][K|V][half of the 16 registers][lane]
+  float knorm[kXBuf][HPW][64];        // squared norm of the scaled key rows (half per lane)
   uint4 wop[HPW][2][D / 16][64];      // projection weights as MFMA operands: [head][K|V][k-slice][lane]
 };
 
@@ -241,6 +243,16 @@ __device__ __forceinline__ void summarize_wave(const MfmaSummarizeParams& p, Sum
 
   f32x16 o[NQB];
   float l[NQB], m[NQB];
+  // plain tiles keep their share of the denominators in lacc (register qb of either accumulator);
+  // the general route folds it into l first
+  static_assert(NQB <= 4, "one accumulator register per query block");
+  f32x4 lacc[2];
+  uint2 onesrow[NQB];
+#pragma unroll
+  for (int r = 0; r < NQB; ++r) {
+    const uint32_t w = (lane & 3) == r ? 0x3F803F80u : 0u;
+    onesrow[r] = make_uint2(w, w);
+  }
   int mode = 0;  // 0 fresh piece, 1 constant reference 0, 2 running maximum
   auto reset_state = [&]() __attribute__((always_inline)) {
 #pragma unroll
@@ -250,6 +262,7 @@ __device__ __forceinline__ void summarize_wave(const MfmaSummarizeParams& p, Sum
       l[qb] = 0.f;
       m[qb] = 0.f;
     }
+    lacc[0] = lacc[1] = f32x4{0.f, 0.f, 0.f, 0.f};
     mode = 0;
   };
 
@@ -307,8 +320,7 @@ __device__ __forceinline__ void summarize_wave(const MfmaSummarizeParams& p, Sum
       if (ROLE == 0) sm.knorm[buf][hl][lane] = n2;
     }
   };
-  auto unsafe_tile = [&](int buf) __attribute__((always_inline)) {
-    const float kn2 = sm.knorm[buf][hl][lane] + sm.knorm[buf][hl][lane ^ 32];
+  auto unsafe_tile = [&](float kn2) __attribute__((always_inline)) {
     return __builtin_amdgcn_ballot_w64(kn2 * qmax2 > kSafeBound2) != 0;
   };
 
@@ -319,9 +331,25 @@ __device__ __forceinline__ void summarize_wave(const MfmaSummarizeParams& p, Sum
   // Common case: a full tile, bounded scores, another tile behind it.  Straight-line
   // code (one scheduling region per tile): two projection MFMAs of the next tile ride
   // along with every query block of this one.
-  auto fast_tile = [&](int buf, int xb, const Pack8& k0, const Pack8& k1, const Pack8& v0,
-                       const Pack8& v1) __attribute__((always_inline)) {   // buf = tile index mod 2, xb = mod 3
-    const int xb_next = xb == kXBuf - 1 ? 0 : xb + 1;
+  Pack8 k0, k1, v0, v1;     // K/V operands of the tile being attended over
+  float kn2;                // its squared key norm (this lane's item)
+  // Operands of tile t+1 (ring slot i1) come out of LDS while tile t is still being worked on,
+  // into the registers tile t has just finished with: K (and the norms) once the last scores
+  // of the tile are issued, V after its last P.V product.  They were published one tile ago
+  // and the barrier at the start of tile t made them visible, so by the next barrier they
+  // are in registers and the next tile starts without a round trip to LDS.
+  auto read_k = [&](int i1) __attribute__((always_inline)) {
+    k0.u = sm.kvbuf[i1][hl][0][0][lane];
+    k1.u = sm.kvbuf[i1][hl][0][1][lane];
+    kn2 = sm.knorm[i1][hl][lane] + sm.knorm[i1][hl][lane ^ 32];
+  };
+  auto read_v = [&](int i1) __attribute__((always_inline)) {
+    v0.u = sm.kvbuf[i1][hl][1][0][lane];
+    v1.u = sm.kvbuf[i1][hl][1][1][lane];
+  };
+  auto fast_tile = [&](int r) __attribute__((always_inline)) {   // r = tile index mod 3
+    const int i1 = r == kXBuf - 1 ? 0 : r + 1;
+    const int i2 = i1 == kXBuf - 1 ? 0 : i1 + 1;
     f32x16 acc = {0};
     // scores run one query block ahead of the exponentials that consume them
     f32x16 nx = {0};
@@ -329,34 +357,53 @@ __device__ __forceinline__ void summarize_wave(const MfmaSummarizeParams& p, Sum
     nx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1.v, qop[0][1], nx, 0, 0, 0);
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) {
+      if (qb == NQB - 1) read_k(i1);     // the last scores of this tile are already issued
       const f32x16 sc = nx;
       if (qb + 1 < NQB) {
         const f32x16 z = {0};
         nx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0.v, qop[qb + 1][0], z, 0, 0, 0);
         nx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1.v, qop[qb + 1][1], nx, 0, 0, 0);
       }
-      if (qb * KPB < KS) project(xb_next, qb * KPB, qb * KPB + KPB, acc);
-      // The denominator adds the weights before their rounding to bf16 (plain adds run
-      // beside the matrix core; the packed dot product does not).
+      if (qb * KPB < KS) project(i2, qb * KPB, qb * KPB + KPB, acc);
       Pack8 p0, p1;
 #pragma unroll
       for (int i = 0; i < 16; i += 2) {
         const float ea = __builtin_amdgcn_exp2f(sc[i]), eb = __builtin_amdgcn_exp2f(sc[i + 1]);
         const uint32_t pk = cvt_pk_bf16(ea, eb);
-        l[qb] += ea + eb;
         if (i < 8) p0.w[i / 2] = pk; else p1.w[(i - 8) / 2] = pk;
+      }
+      // The denominator on the matrix core: a 4x4x4 product (16 blocks, one per four lanes)
+      // whose A block has ones in row qb adds a lane's own four packed weights into register
+      // qb of that lane -- the lane-local partial sum a chain of adds would form, taken over
+      // the bf16 weights the numerator uses.  It issues like one plain vector instruction
+      // for four weights; two accumulators take turns so that consecutive products do not
+      // wait for each other.
+      {
+        const i16x4 sel = __builtin_bit_cast(i16x4, onesrow[qb]);
+#pragma unroll
+        for (int part = 0; part < 4; ++part) {
+          const uint2 pw = part < 2 ? make_uint2(p0.w[2 * part], p0.w[2 * part + 1])
+                                    : make_uint2(p1.w[2 * part - 4], p1.w[2 * part - 3]);
+          lacc[part & 1] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(sel, __builtin_bit_cast(i16x4, pw), lacc[part & 1], 0, 0, 0);
+        }
       }
       o[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v0.v, p0.v, o[qb], 0, 0, 0);
       o[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v1.v, p1.v, o[qb], 0, 0, 0);
     }
-    publish(buf ^ 1, acc);
+    read_v(i1);
+    publish(i2, acc);
   };
 
   // Any tile: ragged tail, scores beyond the bound, last tile of the segment.
-  auto slow_tile = [&](int buf, int xb, int nvalid, bool more, bool unsafe, const Pack8& k0,
-                       const Pack8& k1, const Pack8& v0, const Pack8& v1) __attribute__((always_inline)) {
-    const int xb_next = xb == kXBuf - 1 ? 0 : xb + 1;
+  auto slow_tile = [&](int r, int nvalid, bool unsafe) __attribute__((always_inline)) {
+    const int i1 = r == kXBuf - 1 ? 0 : r + 1;
+    const int i2 = i1 == kXBuf - 1 ? 0 : i1 + 1;
     const int nvl = nvalid - 4 * hf;
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) {
+      l[qb] += lacc[0][qb] + lacc[1][qb];
+      lacc[0][qb] = lacc[1][qb] = 0.f;
+    }
     const bool general = mode == 2 || unsafe;
     if (mode != 2) {   // the reference so far: nothing (fresh piece) or the constant 0
 #pragma unroll
@@ -367,11 +414,12 @@ __device__ __forceinline__ void summarize_wave(const MfmaSummarizeParams& p, Sum
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb)
       attend_block(k0.v, k1.v, v0.v, v1.v, qop[qb][0], qop[qb][1], o[qb], l[qb], m[qb], general, masked, nvl);
-    if (more) {
-      f32x16 acc = {0};
-      project(xb_next, 0, KS, acc);
-      publish(buf ^ 1, acc);
-    }
+    read_k(i1);
+    read_v(i1);
+    // the tile two ahead (past the end of the segment: a repeat of its last tile, never used)
+    f32x16 acc = {0};
+    project(i2, 0, KS, acc);
+    publish(i2, acc);
   };
 
   // partial record of a finished piece: slot = segment + user
@@ -401,7 +449,11 @@ __device__ __forceinline__ void summarize_wave(const MfmaSummarizeParams& p, Sum
     __builtin_amdgcn_s_waitcnt((n & 0xF) | ((n >> 4) << 14) | 0x0F70);
   };
 
-  // ---- prologue: tiles 0, 1, 2 requested; tiles 0 and 1 landed; tile 0 projected
+  // Tile t lives in ring slot t mod 3, as raw rows (xbuf) and, projected, as operands
+  // (kvbuf).  While tile t is attended over, tile t+2 is projected and published, the
+  // operands of tile t+1 move into registers, the rows of tile t+3 land and those of tile
+  // t+4 are requested into the slot whose rows (tile t+1) were projected one tile ago.
+  // ---- prologue: tiles 0, 1, 2 requested; 0 and 1 landed, projected and published
   fetch(cf, 0);
   cursor_advance(cf);
   fetch(cf, 1);
@@ -414,17 +466,26 @@ __device__ __forceinline__ void summarize_wave(const MfmaSummarizeParams& p, Sum
     f32x16 acc = {0};
     project(0, 0, KS, acc);
     publish(0, acc);
+    f32x16 acc1 = {0};
+    project(1, 0, KS, acc1);
+    publish(1, acc1);
   }
+  lds_barrier();              // slot 0's rows are projected by everyone, its operands are visible
+  fetch(cf, 0);               // tile 3
+  cursor_advance(cf);
+  read_k(0);
+  read_v(0);
+  wait_vm(Int<CPT>{});        // tile 2 has landed
 
   // One barrier per tile on either route (waves may take different routes: the bound
   // depends on each wave's queries).  Runs of plain tiles (full, bounded scores, not
   // the last of their piece) stay in the inner loop, whose body is straight-line
   // code with the accumulators updated in place; every other tile leaves it, takes
   // the general route and does the piece bookkeeping.
-  int parity = 0, xb = 0;
-  bool drain = true;      // other vector-memory traffic (record stores, query loads) is in flight
-  // Tile t+2 (requested one tile ago) must have landed before the next barrier; the
-  // request just issued for tile t+3 may stay in flight.  Loads complete in order
+  int r = 0;              // ring slot of the tile being attended over
+  bool drain = false;     // other vector-memory traffic (record stores, query loads) is in flight
+  // Tile t+3 (requested one tile ago) must have landed before the next barrier; the
+  // request just issued for tile t+4 may stay in flight.  Loads complete in order
   // among themselves but not with respect to stores, so after a record write
   // everything is drained once.
   auto end_of_tile = [&]() __attribute__((always_inline)) {
@@ -432,37 +493,31 @@ __device__ __forceinline__ void summarize_wave(const MfmaSummarizeParams& p, Sum
     drain = false;
     cursor_advance(cf);
   };
-  Pack8 k0, k1, v0, v1;
-  bool unsafe;
-  // Start of a tile: request tile t+3, read this tile's K/V operands and key norms in
-  // one burst (LDS answers in order, so the norm test costs no extra round trip).
-  // Returns whether the tile is a plain one.
+  // Start of a tile: the barrier, then the request for tile t+4.
   auto begin_tile = [&]() __attribute__((always_inline)) {
     lds_barrier();
-    fetch(cf, xb);
-    k0.u = sm.kvbuf[parity][hl][0][0][lane];
-    k1.u = sm.kvbuf[parity][hl][0][1][lane];
-    v0.u = sm.kvbuf[parity][hl][1][0][lane];
-    v1.u = sm.kvbuf[parity][hl][1][1][lane];
-    unsafe = unsafe_tile(parity);
-    return !(ca.tiles_left == 1 || mode == 2 || unsafe);
+    fetch(cf, r == kXBuf - 1 ? 0 : r + 1);
   };
-  bool plain = begin_tile();
+  // whether the tile whose operands are in registers is a plain one
+  bool unsafe = unsafe_tile(kn2);
+  auto is_plain = [&]() __attribute__((always_inline)) { return !(ca.tiles_left == 1 || mode == 2 || unsafe); };
+  bool plain = is_plain();
   for (;;) {
     while (__builtin_expect(plain, 1)) {
+      begin_tile();
       mode = 1;
-      fast_tile(parity, xb, k0, k1, v0, v1);
+      fast_tile(r);
       end_of_tile();
       --ca.tiles_left;
       ca.row += kTile;
-      parity ^= 1;
-      xb = xb == kXBuf - 1 ? 0 : xb + 1;
-      plain = begin_tile();
+      r = r == kXBuf - 1 ? 0 : r + 1;
+      unsafe = unsafe_tile(kn2);
+      plain = is_plain();
     }
+    begin_tile();
     const bool last_in_piece = ca.tiles_left == 1;
     const int nvalid = last_in_piece ? ca.tail : kTile;
-    const bool more = !(last_in_piece && ca.wpos >= seg_end);
-    slow_tile(parity, xb, nvalid, more, unsafe, k0, k1, v0, v1);
+    slow_tile(r, nvalid, unsafe);
     end_of_tile();
     const int done_user = ca.user;
     cursor_advance(ca);
@@ -472,10 +527,10 @@ __device__ __forceinline__ void summarize_wave(const MfmaSummarizeParams& p, Sum
       if (p.q_user_stride != 0 && ca.valid) load_queries(ca.user);
       drain = true;
     }
-    parity ^= 1;
-    xb = xb == kXBuf - 1 ? 0 : xb + 1;
+    r = r == kXBuf - 1 ? 0 : r + 1;
     if (!ca.valid) break;
-    plain = begin_tile();
+    unsafe = unsafe_tile(kn2);
+    plain = is_plain();
   }
 }
 
