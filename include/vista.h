@@ -48,8 +48,27 @@ typedef enum {
 
 /* storage dtype of every tensor of a call; accumulation is always fp32 */
 enum { VISTA_F32 = 0, VISTA_BF16 = 1 };
-/* score nonlinearity; only the softmax form of Sec. 3.2.1 is built */
-enum { VISTA_ATTN_SOFTMAX = 0 };
+/*
+ * Attention form of stage 1 (desc.attn):
+ *   VISTA_ATTN_SOFTMAX  RowSoftmax(scale Q_h K_h^T) V_h                      Sec. 3.2.1, unnumbered equation
+ *   VISTA_ATTN_SILU     (1/L_b) sum_j SiLU(scale q . k_j) v_j                App. B, closing formula (SiLU
+ *                       attention from targets to sources) with the 1/N factor of the appendix's opening
+ *                       paragraph, N = the user's own length; the paper prints no score scale, so scale = 0
+ *                       selects 1 here
+ *   VISTA_ATTN_QLA      SiLU(Q_h) SiLU( SiLU(K_h)^T V_h )                    Sec. 3.2.2, target-side QLU equation
+ *                       with the seeds as targets and the history as source; no normalisation, no scale
+ *                       (desc.scale must be 0)
+ */
+enum { VISTA_ATTN_SOFTMAX = 0, VISTA_ATTN_SILU = 1, VISTA_ATTN_QLA = 2 };
+/*
+ * desc.flags.  VISTA_FLAG_SELF_TERM: every query also attends to itself and to no other
+ * query (Eq. 3; the Delta term of Sec. 3.2.2; the identity block of App. B's mask).  In stage 1
+ * the seed's own key and value are seed W_k and seed W_v; in stage 2 (no projections) the
+ * candidate's own embedding is both.  Softmax: the own score joins the row's softmax.  SiLU form:
+ * SiLU(scale q . k') v' joins the sum inside the same 1/L_b.  QLA: (SiLU(q) . SiLU(k')) v' is added.
+ * Users without history still get zeros.
+ */
+enum { VISTA_FLAG_SELF_TERM = 1 };
 
 /* ---------------------------------------------------------------- stage 1 */
 
@@ -65,6 +84,8 @@ typedef struct {
   int64_t total_items;    /* N = offsets[B]                                           */
   int64_t q_user_stride;  /* 0: queries [S,d] shared by all users (Sec. 3.2);
                              S*d: per-user queries [B,S,d] (stacked layers)           */
+  int32_t flags;          /* 0 or VISTA_FLAG_SELF_TERM                                */
+  int32_t reserved;       /* must be 0                                                */
 } vista_summarize_desc;
 
 /*
@@ -188,6 +209,7 @@ typedef struct {
   int32_t H;      /* heads                         */
   int32_t dtype;  /* VISTA_F32 or VISTA_BF16       */
   float   scale;  /* 0 selects 1/sqrt(d/H)         */
+  int32_t flags;  /* 0 or VISTA_FLAG_SELF_TERM     */
 } vista_attend_desc;
 
 /*

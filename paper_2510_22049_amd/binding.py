@@ -22,7 +22,8 @@ VISTA_ERR_NULL, VISTA_ERR_SHAPE, VISTA_ERR_OFFSETS = 1, 2, 3
 VISTA_ERR_UNSUPPORTED, VISTA_ERR_WORKSPACE, VISTA_ERR_HIP, VISTA_ERR_SCRATCH = 4, 5, 6, 7
 VISTA_STATIC_SCRATCH_BYTES = 64 << 20
 VISTA_F32, VISTA_BF16 = 0, 1
-VISTA_ATTN_SOFTMAX = 0
+VISTA_ATTN_SOFTMAX, VISTA_ATTN_SILU, VISTA_ATTN_QLA = 0, 1, 2
+VISTA_FLAG_SELF_TERM = 1
 
 EXPORTS = (
     "vista_status_string",
@@ -40,12 +41,12 @@ class SummarizeDesc(C.Structure):
     _fields_ = [("B", C.c_int32), ("S", C.c_int32), ("d", C.c_int32), ("H", C.c_int32),
                 ("dtype", C.c_int32), ("attn", C.c_int32), ("scale", C.c_float),
                 ("segment_items", C.c_int32), ("total_items", C.c_int64),
-                ("q_user_stride", C.c_int64)]
+                ("q_user_stride", C.c_int64), ("flags", C.c_int32), ("reserved", C.c_int32)]
 
 
 class AttendDesc(C.Structure):
     _fields_ = [("B", C.c_int32), ("C", C.c_int32), ("S", C.c_int32), ("d", C.c_int32),
-                ("H", C.c_int32), ("dtype", C.c_int32), ("scale", C.c_float)]
+                ("H", C.c_int32), ("dtype", C.c_int32), ("scale", C.c_float), ("flags", C.c_int32)]
 
 
 class FfnDesc(C.Structure):
@@ -113,10 +114,12 @@ def _stream() -> int:
     return torch.cuda.current_stream().cuda_stream
 
 
-def summarize_desc(B, S, d, H, dtype, total_items, per_user_q=False, scale=0.0, segment_items=0):
-    return SummarizeDesc(B=B, S=S, d=d, H=H, dtype=dtype, attn=VISTA_ATTN_SOFTMAX, scale=scale,
+def summarize_desc(B, S, d, H, dtype, total_items, per_user_q=False, scale=0.0, segment_items=0,
+                   attn=VISTA_ATTN_SOFTMAX, self_term=False):
+    return SummarizeDesc(B=B, S=S, d=d, H=H, dtype=dtype, attn=attn, scale=scale,
                          segment_items=segment_items, total_items=total_items,
-                         q_user_stride=S * d if per_user_q else 0)
+                         q_user_stride=S * d if per_user_q else 0,
+                         flags=VISTA_FLAG_SELF_TERM if self_term else 0, reserved=0)
 
 
 def vista_summarize_segment_items(desc: SummarizeDesc) -> int:
@@ -144,7 +147,8 @@ def vista_summarize_schedule(desc: SummarizeDesc, offsets_host):
 
 
 def vista_summarize(history_emb, offsets, virtual_queries, W_k, W_v, out, *, H, scale=0.0,
-                    segment_items=0, offsets_host=None, workspace=None):
+                    segment_items=0, offsets_host=None, workspace=None, attn=VISTA_ATTN_SOFTMAX,
+                    self_term=False):
     """Stage 1.  history_emb [N,d], offsets int64 [B+1] (device), virtual_queries
     [S,d] or [B,S,d], W_k/W_v [d,d], out [B,S,d]; all on the GPU, same dtype.
     ``workspace`` is a uint8 device tensor (allocated here when None, by torch)."""
@@ -152,7 +156,7 @@ def vista_summarize(history_emb, offsets, virtual_queries, W_k, W_v, out, *, H, 
     S, d = virtual_queries.shape[-2:]
     N = history_emb.shape[0]
     desc = summarize_desc(B, S, d, H, _dtype_code(history_emb), N, virtual_queries.dim() == 3, scale,
-                          segment_items)
+                          segment_items, attn, self_term)
     need = vista_summarize_workspace_bytes(desc)
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=history_emb.device)
@@ -173,13 +177,13 @@ def vista_summarize(history_emb, offsets, virtual_queries, W_k, W_v, out, *, H, 
 
 
 def vista_summarize_static(history_emb, offsets, virtual_queries, W_k, W_v, out, *, H, scale=0.0,
-                           segment_items=0, offsets_host=None):
+                           segment_items=0, offsets_host=None, attn=VISTA_ATTN_SOFTMAX, self_term=False):
     """Stage 1 on the library's static scratch: no workspace argument, nothing allocated."""
     B = offsets.numel() - 1
     S, d = virtual_queries.shape[-2:]
     N = history_emb.shape[0]
     desc = summarize_desc(B, S, d, H, _dtype_code(history_emb), N, virtual_queries.dim() == 3, scale,
-                          segment_items)
+                          segment_items, attn, self_term)
     host = None
     if offsets_host is not None:
         if offsets_host.is_cuda or offsets_host.dtype != torch.int64:
@@ -194,11 +198,12 @@ def vista_summarize_static(history_emb, offsets, virtual_queries, W_k, W_v, out,
         raise VistaError(st)
 
 
-def vista_target_attend(candidates, summaries, out, *, H, scale=0.0):
+def vista_target_attend(candidates, summaries, out, *, H, scale=0.0, self_term=False):
     """Stage 2.  candidates [B,C,d], summaries [B,S,d], out [B,C,d]; device, same dtype."""
     B, Cn, d = candidates.shape
     S = summaries.shape[1]
-    desc = AttendDesc(B=B, C=Cn, S=S, d=d, H=H, dtype=_dtype_code(candidates), scale=scale)
+    desc = AttendDesc(B=B, C=Cn, S=S, d=d, H=H, dtype=_dtype_code(candidates), scale=scale,
+                      flags=VISTA_FLAG_SELF_TERM if self_term else 0)
     st = lib().vista_target_attend(C.byref(desc), _dev(candidates, "candidates"),
                                    _dev(summaries, "summaries"), _dev(out, "out"), _stream())
     if st != VISTA_OK:

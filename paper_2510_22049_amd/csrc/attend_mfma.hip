@@ -403,7 +403,7 @@ hipError_t launch_attend(const AttendParams& p, hipStream_t s) {
 }  // namespace
 
 bool mfma_target_attend_supported(const vista_attend_desc& d) {
-  return d.dtype == VISTA_BF16 && d.d == 32 * d.H && d.H % kHeads == 0 && d.S % 32 == 0 && (d.S <= 256 || (d.S % 64 == 0 && d.S <= 512)) &&
+  return d.dtype == VISTA_BF16 && d.flags == 0 && d.d == 32 * d.H && d.H % kHeads == 0 && d.S % 32 == 0 && (d.S <= 256 || (d.S % 64 == 0 && d.S <= 512)) &&
          int64_t(d.C) * d.d * 2 < (int64_t(1) << 32);
 }
 

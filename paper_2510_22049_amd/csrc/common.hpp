@@ -165,6 +165,7 @@ struct SummarizeArgs {
   int64_t G;          // segments
   const int* seg_user; // [G] first user of each segment (written by the plan kernel); null: found in the kernel
   float scale_log2;   // scale * log2(e)
+  float scale_plain;  // scale
   const void* X;
   const int64_t* offsets;
   const void* Q;
@@ -176,6 +177,9 @@ struct SummarizeArgs {
 };
 
 size_t generic_summarize_workspace(const vista_summarize_desc& d, int seg);
+size_t self_kv_bytes(const vista_summarize_desc& d);
+hipError_t launch_self_kv(const vista_summarize_desc& d, const void* Q, const void* Wk, const void* Wv, float* Ks,
+                          float* Vs, hipStream_t s);
 vista_status generic_summarize(const SummarizeArgs& a);
 bool mfma_summarize_supported(const vista_summarize_desc& d);
 size_t mfma_summarize_workspace(const vista_summarize_desc& d, int seg);

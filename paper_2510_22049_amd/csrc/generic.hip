@@ -73,7 +73,10 @@ __global__ void project_kernel(const T* __restrict__ X, const T* __restrict__ Wk
 // ------------------------------------------- stage 1: streaming attention
 // Partial slot layout: [slot][h][query][dh + 2] fp32 = un-normalised O, then
 // l (sum of 2^(s-m)) and m (running maximum of s, base-2 units).
-template <typename T>
+// SILU = true: the pointwise score form of App. B, o += SiLU(s) v with no maximum and no
+// denominator (the record's l and m stay 0; the merge divides by the user's length).  The
+// score then arrives in natural units (scale_log2 carries the plain scale).
+template <typename T, bool SILU>
 __global__ void attend_history_kernel(const float* __restrict__ K, const float* __restrict__ V,
                                       const T* __restrict__ Q, int64_t q_user_stride,
                                       const int64_t* __restrict__ offsets, int B, int S, int d, int H,
@@ -96,36 +99,79 @@ __global__ void attend_history_kernel(const float* __restrict__ K, const float* 
         o[t] = 0.f;
       }
       float m = -INFINITY, l = 0.f;
+      (void)m; (void)l;
       for (int64_t j = pc.begin; j < pc.end; ++j) {
         const float* kr = K + j * d + h * dh;
         const float* vr = V + j * d + h * dh;
         float s = 0.f;
         for (int t = 0; t < kMaxDh; ++t)
           if (t < dh) s = fmaf(q[t], kr[t], s);
-        float mn = fmaxf(m, s);
-        float alpha = exp2f(m - mn);  // exp2(-inf) = 0 on the first item
-        float p = exp2f(s - mn);
-        l = l * alpha + p;
-        for (int t = 0; t < kMaxDh; ++t)
-          if (t < dh) o[t] = fmaf(o[t], alpha, p * vr[t]);
-        m = mn;
+        if (SILU) {
+          const float p = s / (1.f + expf(-s));
+          for (int t = 0; t < kMaxDh; ++t)
+            if (t < dh) o[t] = fmaf(p, vr[t], o[t]);
+        } else {
+          float mn = fmaxf(m, s);
+          float alpha = exp2f(m - mn);  // exp2(-inf) = 0 on the first item
+          float p = exp2f(s - mn);
+          l = l * alpha + p;
+          for (int t = 0; t < kMaxDh; ++t)
+            if (t < dh) o[t] = fmaf(o[t], alpha, p * vr[t]);
+          m = mn;
+        }
       }
       float* dst = partials + ((slot * H + h) * S + i) * (dh + 2);
       for (int t = 0; t < kMaxDh; ++t)
         if (t < dh) dst[t] = o[t];
-      dst[dh] = l;
-      dst[dh + 1] = m;
+      dst[dh] = SILU ? 0.f : l;
+      dst[dh + 1] = SILU ? 0.f : m;
     }
   }
 }
 
-// ------------------------------------------------------- stage 1: merge
-// Combines a user's partial slots in ascending segment order:
-//   m = max m_c,  l = sum l_c 2^(m_c - m),  O = sum O_c 2^(m_c - m),  out = O / l.
-// grid (B, H); threads stride over (query, channel).
+// ---------------------------------------- seeds as their own key and value
+// Self term (Eq. 3; the Delta term of Sec. 3.2.2): K' = Q W_k, V' = Q W_v in fp32 for the
+// S shared seeds or the B*S per-user ones.  One thread per (row, column).
 template <typename T>
+__global__ void self_kv_kernel(const T* __restrict__ Q, const T* __restrict__ Wk, const T* __restrict__ Wv,
+                               float* __restrict__ Ks, float* __restrict__ Vs, int64_t rows, int d) {
+  int64_t idx = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (idx >= rows * d) return;
+  const int64_t row = idx / d;
+  const int col = int(idx - row * d);
+  const T* q = Q + row * d;
+  float k = 0.f, v = 0.f;
+  for (int t = 0; t < d; ++t) {
+    const float qv = to_f32(q[t]);
+    k = fmaf(qv, to_f32(Wk[int64_t(t) * d + col]), k);
+    v = fmaf(qv, to_f32(Wv[int64_t(t) * d + col]), v);
+  }
+  Ks[idx] = k;
+  Vs[idx] = v;
+}
+
+hipError_t launch_self_kv(const vista_summarize_desc& d, const void* Q, const void* Wk, const void* Wv, float* Ks,
+                          float* Vs, hipStream_t s) {
+  const int64_t rows = d.q_user_stride ? int64_t(d.B) * d.S : d.S;
+  const int64_t blocks = (rows * d.d + 255) / 256;
+  if (d.dtype == VISTA_BF16)
+    return launch(self_kv_kernel<bf16_t>, dim3(unsigned(blocks)), dim3(256), 0, s, static_cast<const bf16_t*>(Q),
+                  static_cast<const bf16_t*>(Wk), static_cast<const bf16_t*>(Wv), Ks, Vs, rows, d.d);
+  return launch(self_kv_kernel<float>, dim3(unsigned(blocks)), dim3(256), 0, s, static_cast<const float*>(Q),
+                static_cast<const float*>(Wk), static_cast<const float*>(Wv), Ks, Vs, rows, d.d);
+}
+
+// ------------------------------------------------------- stage 1: merge
+// Combines a user's partial slots in ascending segment order.
+//   softmax:  m = max m_c,  l = sum l_c 2^(m_c - m),  O = sum O_c 2^(m_c - m),  out = O / l;
+//             the self term is one more slot: m = own score, l = 1, O = own value;
+//   SiLU form: out = (sum O_c [+ SiLU(own score) own value]) / L_b.
+// grid (B, H); threads stride over (query, channel).  scale_log2 / scale as in the main kernel.
+template <typename T, bool SILU>
 __global__ void merge_kernel(const float* __restrict__ partials, const int64_t* __restrict__ offsets,
-                             int S, int d, int H, int seg, int64_t G, T* __restrict__ out) {
+                             int S, int d, int H, int seg, int64_t G, T* __restrict__ out,
+                             const T* __restrict__ Q, int64_t q_user_stride, const float* __restrict__ Ks,
+                             const float* __restrict__ Vs, float scale_log2) {
   const int dh = d / H;
   const int b = blockIdx.x, h = blockIdx.y;
   const int64_t begin = offsets[b], end = offsets[b + 1];
@@ -137,9 +183,25 @@ __global__ void merge_kernel(const float* __restrict__ partials, const int64_t* 
   int64_t g0 = begin / seg, g1 = (end - 1) / seg;
   if (g0 < 0) g0 = 0;
   if (g1 > G - 1) g1 = G - 1;
+  const int64_t srow0 = q_user_stride ? int64_t(b) * S : 0;     // first row of this user's K', V'
   for (int e = threadIdx.x; e < S * dh; e += blockDim.x) {
     const int i = e / dh, t = e % dh;
-    float m = -INFINITY;
+    float s_self = 0.f, v_self = 0.f;
+    if (Ks) {
+      const T* q = Q + q_user_stride * b + int64_t(i) * d + h * dh;
+      const float* ks = Ks + (srow0 + i) * d + h * dh;
+      for (int c = 0; c < dh; ++c) s_self = fmaf(to_f32(q[c]), ks[c], s_self);
+      s_self *= scale_log2;
+      v_self = Vs[(srow0 + i) * d + h * dh + t];
+    }
+    if (SILU) {
+      float o = 0.f;
+      for (int64_t g = g0; g <= g1; ++g) o += partials[(((g + b) * H + h) * S + i) * (dh + 2) + t];
+      if (Ks) o = fmaf(s_self / (1.f + expf(-s_self)), v_self, o);
+      store_as(dst + int64_t(i) * d + t, o / float(end - begin));
+      continue;
+    }
+    float m = Ks ? s_self : -INFINITY;
     for (int64_t g = g0; g <= g1; ++g) {
       const float* p = partials + (((g + b) * H + h) * S + i) * (dh + 2);
       m = fmaxf(m, p[dh + 1]);
@@ -151,14 +213,98 @@ __global__ void merge_kernel(const float* __restrict__ partials, const int64_t* 
       l = fmaf(p[dh], w, l);
       o = fmaf(p[t], w, o);
     }
+    if (Ks) {
+      const float w = exp2f(s_self - m);
+      l += w;
+      o = fmaf(v_self, w, o);
+    }
     store_as(dst + int64_t(i) * d + t, o / l);
+  }
+}
+
+// ---------------------------------------------- quasi-linear attention (plain path)
+// State of one piece: Z_h = SiLU(K_h)^T V_h, [dh x dh] fp32 per (slot, head) (Sec. 3.2.2; the
+// block sums of App. B).  grid (G, H), 256 threads stride over the dh*dh entries.
+__global__ void qla_state_kernel(const float* __restrict__ K, const float* __restrict__ V,
+                                 const int64_t* __restrict__ offsets, int B, int d, int H, int64_t N, int seg,
+                                 const int* __restrict__ seg_user, float* __restrict__ partials) {
+  const int dh = d / H;
+  const int h = blockIdx.y;
+  const int64_t seg_begin = int64_t(blockIdx.x) * seg;
+  const int64_t seg_end = (seg_begin + seg < N) ? seg_begin + seg : N;
+  int user = seg_user[blockIdx.x];
+  int64_t pos = seg_begin;
+  Piece pc;
+  while (next_piece(offsets, B, seg_end, user, pos, pc)) {
+    const int64_t slot = int64_t(blockIdx.x) + pc.user;
+    for (int e = threadIdx.x; e < dh * dh; e += blockDim.x) {
+      const int a = e / dh, c = e % dh;
+      float z = 0.f;
+      for (int64_t j = pc.begin; j < pc.end; ++j) {
+        const float k = K[j * d + h * dh + a];
+        z = fmaf(k / (1.f + expf(-k)), V[j * d + h * dh + c], z);
+      }
+      partials[(slot * H + h) * dh * dh + e] = z;
+    }
+  }
+}
+
+// out_h = SiLU(Q_h) SiLU(Z_h) with Z_h the ascending-order sum of the user's states;
+// the self term adds (SiLU(q) . SiLU(k')) v'.  grid (B, H), Z staged in LDS.
+template <typename T>
+__global__ void qla_finish_kernel(const float* __restrict__ partials, const int64_t* __restrict__ offsets, int S,
+                                  int d, int H, int seg, int64_t G, T* __restrict__ out, const T* __restrict__ Q,
+                                  int64_t q_user_stride, const float* __restrict__ Ks,
+                                  const float* __restrict__ Vs) {
+  __shared__ float z[kMaxDh * kMaxDh];
+  const int dh = d / H;
+  const int b = blockIdx.x, h = blockIdx.y;
+  const int64_t begin = offsets[b], end = offsets[b + 1];
+  T* dst = out + int64_t(b) * S * d + h * dh;
+  if (end <= begin) {
+    for (int e = threadIdx.x; e < S * dh; e += blockDim.x) store_as(dst + int64_t(e / dh) * d + (e % dh), 0.f);
+    return;
+  }
+  int64_t g0 = begin / seg, g1 = (end - 1) / seg;
+  if (g0 < 0) g0 = 0;
+  if (g1 > G - 1) g1 = G - 1;
+  for (int e = threadIdx.x; e < dh * dh; e += blockDim.x) {
+    float acc = 0.f;
+    for (int64_t g = g0; g <= g1; ++g) acc += partials[((g + b) * H + h) * dh * dh + e];
+    z[e] = acc / (1.f + expf(-acc));
+  }
+  __syncthreads();
+  const int64_t srow0 = q_user_stride ? int64_t(b) * S : 0;
+  for (int e = threadIdx.x; e < S * dh; e += blockDim.x) {
+    const int i = e / dh, t = e % dh;
+    const T* q = Q + q_user_stride * b + int64_t(i) * d + h * dh;
+    float o = 0.f, dot = 0.f;
+    for (int a = 0; a < dh; ++a) {
+      const float qa = to_f32(q[a]);
+      const float pa = qa / (1.f + expf(-qa));
+      o = fmaf(pa, z[a * dh + t], o);
+      if (Ks) {
+        const float k = Ks[(srow0 + i) * d + h * dh + a];
+        dot = fmaf(pa, k / (1.f + expf(-k)), dot);
+      }
+    }
+    if (Ks) o = fmaf(dot, Vs[(srow0 + i) * d + h * dh + t], o);
+    store_as(dst + int64_t(i) * d + t, o);
   }
 }
 
 static size_t generic_partials_bytes(const vista_summarize_desc& d, int seg) {
   int64_t G = (d.total_items + seg - 1) / seg;
   int dh = d.d / d.H;
+  if (d.attn == VISTA_ATTN_QLA) return size_t(G + d.B) * d.H * dh * dh * sizeof(float);
   return size_t(G + d.B) * d.H * d.S * (dh + 2) * sizeof(float);
+}
+
+// fp32 K' and V' of the seeds (self term), each [S or B*S, d]; 0 without the flag
+size_t self_kv_bytes(const vista_summarize_desc& d) {
+  if (!(d.flags & VISTA_FLAG_SELF_TERM)) return 0;
+  const size_t rows = d.q_user_stride ? size_t(d.B) * d.S : size_t(d.S);
+  return (rows * d.d * sizeof(float) + 255) & ~size_t(255);
 }
 
 static size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
@@ -166,7 +312,7 @@ static size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
 size_t generic_summarize_workspace(const vista_summarize_desc& d, int seg) {
   const int64_t G = (d.total_items + seg - 1) / seg;
   return kHeaderBytes + plan_bytes(G) + align256(generic_partials_bytes(d, seg)) +
-         2 * align256(size_t(d.total_items) * d.d * sizeof(float));
+         2 * align256(size_t(d.total_items) * d.d * sizeof(float)) + 2 * self_kv_bytes(d);
 }
 
 template <typename T>
@@ -177,6 +323,17 @@ static vista_status generic_summarize_t(const SummarizeArgs& a) {
   float* partials = reinterpret_cast<float*>(base);
   float* K = reinterpret_cast<float*>(base + align256(generic_partials_bytes(d, a.seg)));
   float* V = K + align256(size_t(N) * d.d * sizeof(float)) / sizeof(float);
+  float* Ks = nullptr;
+  float* Vs = nullptr;
+  if (d.flags & VISTA_FLAG_SELF_TERM) {
+    Ks = V + align256(size_t(N) * d.d * sizeof(float)) / sizeof(float);
+    Vs = Ks + self_kv_bytes(d) / sizeof(float);
+    if (launch_self_kv(d, a.Q, a.Wk, a.Wv, Ks, Vs, a.stream) != hipSuccess) return VISTA_ERR_HIP;
+  }
+  const T* Q = static_cast<const T*>(a.Q);
+  const bool silu = d.attn == VISTA_ATTN_SILU, qla = d.attn == VISTA_ATTN_QLA;
+  // the softmax form works in base-2 units; the pointwise forms take the score as it is
+  const float score_scale = silu ? a.scale_plain : a.scale_log2;
   if (N > 0) {
     int64_t total = N * d.d;
     int64_t blocks = (total + 255) / 256;
@@ -184,12 +341,26 @@ static vista_status generic_summarize_t(const SummarizeArgs& a) {
     VISTA_LAUNCH(project_kernel<T>, dim3(unsigned(blocks)), dim3(256), 0, a.stream,
                        static_cast<const T*>(a.X), static_cast<const T*>(a.Wk), static_cast<const T*>(a.Wv),
                        K, V, N, d.d);
-    VISTA_LAUNCH(attend_history_kernel<T>, dim3(unsigned(a.G), d.H), dim3(64), 0, a.stream, K, V,
-                       static_cast<const T*>(a.Q), d.q_user_stride, a.offsets, d.B, d.S, d.d, d.H,
-                       a.scale_log2, N, a.seg, a.seg_user, partials);
+    if (qla)
+      VISTA_LAUNCH(qla_state_kernel, dim3(unsigned(a.G), d.H), dim3(256), 0, a.stream, K, V, a.offsets, d.B, d.d,
+                   d.H, N, a.seg, a.seg_user, partials);
+    else if (silu)
+      VISTA_LAUNCH((attend_history_kernel<T, true>), dim3(unsigned(a.G), d.H), dim3(64), 0, a.stream, K, V, Q,
+                   d.q_user_stride, a.offsets, d.B, d.S, d.d, d.H, score_scale, N, a.seg, a.seg_user, partials);
+    else
+      VISTA_LAUNCH((attend_history_kernel<T, false>), dim3(unsigned(a.G), d.H), dim3(64), 0, a.stream, K, V, Q,
+                   d.q_user_stride, a.offsets, d.B, d.S, d.d, d.H, score_scale, N, a.seg, a.seg_user, partials);
   }
-  VISTA_LAUNCH(merge_kernel<T>, dim3(d.B, d.H), dim3(256), 0, a.stream, partials, a.offsets, d.S, d.d,
-                     d.H, a.seg, a.G, static_cast<T*>(a.out));
+  T* out = static_cast<T*>(a.out);
+  if (qla)
+    VISTA_LAUNCH(qla_finish_kernel<T>, dim3(d.B, d.H), dim3(256), 0, a.stream, partials, a.offsets, d.S, d.d, d.H,
+                 a.seg, a.G, out, Q, d.q_user_stride, Ks, Vs);
+  else if (silu)
+    VISTA_LAUNCH((merge_kernel<T, true>), dim3(d.B, d.H), dim3(256), 0, a.stream, partials, a.offsets, d.S, d.d,
+                 d.H, a.seg, a.G, out, Q, d.q_user_stride, Ks, Vs, score_scale);
+  else
+    VISTA_LAUNCH((merge_kernel<T, false>), dim3(d.B, d.H), dim3(256), 0, a.stream, partials, a.offsets, d.S, d.d,
+                 d.H, a.seg, a.G, out, Q, d.q_user_stride, Ks, Vs, score_scale);
   return VISTA_OK;
 }
 
@@ -203,7 +374,7 @@ vista_status generic_summarize(const SummarizeArgs& a) {
 template <typename T>
 __global__ void target_attend_kernel(const T* __restrict__ cand, const T* __restrict__ summ,
                                      T* __restrict__ out, int64_t total, int C, int S, int d, int H,
-                                     float scale_log2) {
+                                     float scale_log2, int self_term) {
   const int dh = d / H;
   int64_t idx = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
   if (idx >= total) return;
@@ -218,8 +389,9 @@ __global__ void target_attend_kernel(const T* __restrict__ cand, const T* __rest
     o[t] = 0.f;
   }
   float m = -INFINITY, l = 0.f;
-  for (int j = 0; j < S; ++j) {
-    const T* y = Y + int64_t(j) * d;
+  // with the self term the candidate's own embedding is one more key and value (Eq. 3)
+  for (int j = 0; j < S + (self_term ? 1 : 0); ++j) {
+    const T* y = j < S ? Y + int64_t(j) * d : qrow;
     float s = 0.f;
     for (int t = 0; t < kMaxDh; ++t)
       if (t < dh) s = fmaf(q[t], to_f32(y[t]), s);
@@ -246,11 +418,13 @@ vista_status generic_target_attend(const vista_attend_desc& d, float scale_log2,
   if (d.dtype == VISTA_BF16)
     VISTA_LAUNCH(target_attend_kernel<bf16_t>, dim3(unsigned(blocks)), dim3(128), 0, s,
                        static_cast<const bf16_t*>(cand), static_cast<const bf16_t*>(summ),
-                       static_cast<bf16_t*>(out), total, d.C, d.S, d.d, d.H, scale_log2);
+                       static_cast<bf16_t*>(out), total, d.C, d.S, d.d, d.H, scale_log2,
+                       int(d.flags & VISTA_FLAG_SELF_TERM));
   else
     VISTA_LAUNCH(target_attend_kernel<float>, dim3(unsigned(blocks)), dim3(128), 0, s,
                        static_cast<const float*>(cand), static_cast<const float*>(summ),
-                       static_cast<float*>(out), total, d.C, d.S, d.d, d.H, scale_log2);
+                       static_cast<float*>(out), total, d.C, d.S, d.d, d.H, scale_log2,
+                       int(d.flags & VISTA_FLAG_SELF_TERM));
   return VISTA_OK;
 }
 

@@ -654,7 +654,7 @@ static bool shape_d128(const vista_summarize_desc& d) { return d.d == 128 && d.H
 static bool shape_d256(const vista_summarize_desc& d) { return d.d == 256 && d.H == 8; }
 
 bool mfma_summarize_supported(const vista_summarize_desc& d) {
-  if (d.dtype != VISTA_BF16) return false;
+  if (d.dtype != VISTA_BF16 || d.attn != VISTA_ATTN_SOFTMAX || d.flags != 0) return false;
   if (!(shape_d128(d) || shape_d256(d))) return false;
   return d.S == 64 || d.S == 128 || d.S == 256 || d.S == 512;
 }

@@ -20,7 +20,10 @@ vista_status check_summarize_desc(const vista_summarize_desc* d) {
   if (d->q_user_stride != 0 && d->q_user_stride != int64_t(d->S) * d->d) return VISTA_ERR_SHAPE;
   if (d->segment_items < 0 || d->segment_items % 32 != 0) return VISTA_ERR_SHAPE;
   if (!(d->scale >= 0.f) || isinf(d->scale)) return VISTA_ERR_SHAPE;
-  if (!dtype_ok(d->dtype) || d->attn != VISTA_ATTN_SOFTMAX) return VISTA_ERR_UNSUPPORTED;
+  if (d->attn < VISTA_ATTN_SOFTMAX || d->attn > VISTA_ATTN_QLA) return VISTA_ERR_UNSUPPORTED;
+  if ((d->flags & ~VISTA_FLAG_SELF_TERM) != 0 || d->reserved != 0) return VISTA_ERR_SHAPE;
+  if (d->attn == VISTA_ATTN_QLA && d->scale != 0.f) return VISTA_ERR_SHAPE;
+  if (!dtype_ok(d->dtype)) return VISTA_ERR_UNSUPPORTED;
   if (d->S > 512 || d->d > 512 || d->d / d->H > 64) return VISTA_ERR_UNSUPPORTED;
   return VISTA_OK;
 }
@@ -142,8 +145,12 @@ vista_status vista_summarize(const vista_summarize_desc* desc, const void* histo
   a.seg = resolve_segment(desc);
   a.G = (desc->total_items + a.seg - 1) / a.seg;
   if (a.G + desc->B > 0x7FFFFFFF) return VISTA_ERR_UNSUPPORTED;
-  const float scale = desc->scale > 0.f ? desc->scale : 1.f / sqrtf(float(desc->d / desc->H));
+  // default scale: 1/sqrt(d_h) for the softmax form, none for the pointwise forms (as printed)
+  const float scale = desc->scale > 0.f                  ? desc->scale
+                      : desc->attn == VISTA_ATTN_SOFTMAX ? 1.f / sqrtf(float(desc->d / desc->H))
+                                                         : 1.f;
   a.scale_log2 = scale * kLog2e;
+  a.scale_plain = scale;
   a.X = history_emb;
   a.offsets = offsets;
   a.Q = virtual_queries;
@@ -189,6 +196,7 @@ vista_status vista_target_attend(const vista_attend_desc* desc, const void* cand
   if (desc->B <= 0 || desc->C <= 0 || desc->S <= 0 || desc->d <= 0 || desc->H <= 0) return VISTA_ERR_SHAPE;
   if (desc->d % desc->H != 0) return VISTA_ERR_SHAPE;
   if (!(desc->scale >= 0.f) || isinf(desc->scale)) return VISTA_ERR_SHAPE;
+  if ((desc->flags & ~VISTA_FLAG_SELF_TERM) != 0) return VISTA_ERR_SHAPE;
   if (!dtype_ok(desc->dtype)) return VISTA_ERR_UNSUPPORTED;
   if (desc->S > 512 || desc->d / desc->H > 64) return VISTA_ERR_UNSUPPORTED;
   if (!candidates || !summaries || !out) return VISTA_ERR_NULL;

@@ -1,0 +1,81 @@
+"""GPU parity of the further attention forms -- the SiLU score form (App. B), quasi-linear
+attention (Sec. 3.2.2) and the self term (Eq. 3) -- against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import vista_oracle as O
+from paper_2510_22049_amd import binding as V
+from paper_2510_22049_amd import inputs as I
+from tests.helpers import assert_blocks_close, dev, host64, torch_dtype
+
+pytestmark = pytest.mark.gpu
+
+LENS = [700, 0, 1, 31, 32, 33, 2100, 64, 0, 95, 1029]
+FORMS = {"softmax": V.VISTA_ATTN_SOFTMAX, "silu": V.VISTA_ATTN_SILU, "qla": V.VISTA_ATTN_QLA}
+
+
+def oracle(form, X, off, Q, Wk, Wv, H, self_term, scale=None):
+    if form == "softmax":
+        return O.summarize(X, off, Q, Wk, Wv, H, scale=scale, self_term=self_term)
+    if form == "silu":
+        return O.summarize_silu(X, off, Q, Wk, Wv, H, scale=scale, self_term=self_term)
+    return O.summarize_qla(X, off, Q, Wk, Wv, H, self_term=self_term)
+
+
+def problem(seed, lens, d, S, dtype, per_user=False, qscale=1.0):
+    g = np.random.default_rng(seed)
+    off = I.offsets_from_lengths(lens)
+    r = lambda shape, s=1.0: I.round_to((g.normal(size=shape) * s).astype(np.float32), dtype)
+    return (r((off[-1], d)), off, r((len(lens), S, d) if per_user else (S, d), qscale),
+            r((d, d), d ** -0.5), r((d, d), d ** -0.5))
+
+
+def run(form, X, off, Q, Wk, Wv, H, dtype, self_term=False, **kw):
+    B = len(off) - 1
+    S, d = Q.shape[-2:]
+    out = torch.full((B, S, d), float("nan"), device="cuda", dtype=torch_dtype(dtype))
+    offd = torch.from_numpy(np.asarray(off, dtype=np.int64)).cuda()
+    ws = V.vista_summarize(dev(X, dtype), offd, dev(Q, dtype), dev(Wk, dtype), dev(Wv, dtype), out, H=H,
+                           attn=FORMS[form], self_term=self_term, **kw)
+    torch.cuda.synchronize()
+    assert int(ws[:4].view(torch.int32).item()) == 0
+    return host64(out)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("form,self_term", [("silu", False), ("silu", True), ("qla", False), ("qla", True),
+                                            ("softmax", True)])
+@pytest.mark.parametrize("H,d,S,per_user", [(2, 64, 24, False), (4, 64, 40, True), (1, 48, 7, False)])
+def test_plain_path_forms(dtype, form, self_term, H, d, S, per_user):
+    """Empty, single-item, ragged and multi-segment users on the fp32-ALU kernels."""
+    X, off, Q, Wk, Wv = problem(H * 100 + S, LENS, d, S, dtype, per_user)
+    got = run(form, X, off, Q, Wk, Wv, H, dtype, self_term, segment_items=64)
+    want = oracle(form, X, off, Q, Wk, Wv, H, self_term)
+    assert_blocks_close(got, want, dtype, f"{form} self={self_term} {dtype}")
+    assert np.all(got[1] == 0) and np.all(got[8] == 0)
+
+
+def test_silu_form_scale_override_and_default():
+    X, off, Q, Wk, Wv = problem(3, [300, 17, 900], 64, 16, "f32")
+    got = run("silu", X, off, Q, Wk, Wv, 2, "f32", scale=0.25)
+    assert_blocks_close(got, O.summarize_silu(X, off, Q, Wk, Wv, 2, scale=0.25), "f32", "silu scale 0.25")
+    got = run("silu", X, off, Q, Wk, Wv, 2, "f32")                  # scale 0: none, as the paper prints the form
+    assert_blocks_close(got, O.summarize_silu(X, off, Q, Wk, Wv, 2, scale=1.0), "f32", "silu default scale")
+
+
+def test_qla_rejects_a_score_scale():
+    X, off, Q, Wk, Wv = problem(4, [50], 64, 16, "f32")
+    with pytest.raises(V.VistaError):
+        run("qla", X, off, Q, Wk, Wv, 2, "f32", scale=0.5)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_stage2_self_term_plain_path(dtype):
+    g = np.random.default_rng(5)
+    r = lambda shape: I.round_to(g.normal(size=shape).astype(np.float32), dtype)
+    T, Y = r((3, 19, 64)), r((3, 24, 64))
+    out = torch.full(T.shape, float("nan"), device="cuda", dtype=torch_dtype(dtype))
+    V.vista_target_attend(dev(T, dtype), dev(Y, dtype), out, H=2, self_term=True)
+    torch.cuda.synchronize()
+    assert_blocks_close(host64(out), O.target_attend(T, Y, 2, self_term=True), dtype, "stage 2 self term")
