@@ -159,11 +159,17 @@ struct SummarizeLds {
 // issues the projection MFMAs of tile t+1, and the X rows of tiles t+2 / t+3 are
 // on their way from HBM (registers) into the LDS buffer tile t has vacated.  One
 // LDS-only barrier per tile orders the two double-buffered exchanges.
-template <int D, int NQB, int HPW, int ROLE, int WPH = 2>
+// ATTN selects what is made of a score: VISTA_ATTN_SOFTMAX as described above, or
+// VISTA_ATTN_SILU, the pointwise form SiLU(s) v of App. B: no reference maximum, no
+// denominator, no norm test; the key weights then carry -scale*log2(e), so a score leaves the
+// MFMA as t = -s log2(e) and SiLU(s) = -ln(2) t / (1 + 2^t); the weight handed to the second
+// product is t / (1 + 2^t) and the constant joins the 1/L_b of the merge.
+template <int D, int NQB, int HPW, int ROLE, int WPH = 2, int ATTN = VISTA_ATTN_SOFTMAX>
 __device__ __forceinline__ void summarize_wave(const MfmaSummarizeParams& p, SummarizeLds<D, HPW>& sm,
                                                int64_t g, int h, int hl, int qslot, int64_t seg_begin,
                                                int64_t seg_end) {
   constexpr bool PROJ = ROLE < 2;        // this wave projects
+  constexpr bool SILU = ATTN == VISTA_ATTN_SILU;
   constexpr int WR = PROJ ? ROLE : 0;    // its slot in the weight and K/V buffers (unused otherwise)
   constexpr int NT = HPW * WPH * 64;     // threads
   constexpr int CH = D / 8;              // 16-byte chunks per row
@@ -312,15 +318,16 @@ __device__ __forceinline__ void summarize_wave(const MfmaSummarizeParams& p, Sum
 #pragma unroll
       for (int i = 0; i < 16; i += 2) {
         const uint32_t pk = cvt_pk_bf16(acc[i], acc[i + 1]);
-        if (ROLE == 0) n2 = dot2_self(pk, n2);
+        if (ROLE == 0 && !SILU) n2 = dot2_self(pk, n2);
         if (i < 8) r0.w[i / 2] = pk; else r1.w[(i - 8) / 2] = pk;
       }
       sm.kvbuf[buf][hl][WR][0][lane] = r0.u;
       sm.kvbuf[buf][hl][WR][1][lane] = r1.u;
-      if (ROLE == 0) sm.knorm[buf][hl][lane] = n2;
+      if (ROLE == 0 && !SILU) sm.knorm[buf][hl][lane] = n2;
     }
   };
   auto unsafe_tile = [&](float kn2) __attribute__((always_inline)) {
+    if constexpr (SILU) return false;
     return __builtin_amdgcn_ballot_w64(kn2 * qmax2 > kSafeBound2) != 0;
   };
 
@@ -332,7 +339,7 @@ __device__ __forceinline__ void summarize_wave(const MfmaSummarizeParams& p, Sum
   // code (one scheduling region per tile): two projection MFMAs of the next tile ride
   // along with every query block of this one.
   Pack8 k0, k1, v0, v1;     // K/V operands of the tile being attended over
-  float kn2;                // its squared key norm (this lane's item)
+  float kn2 = 0.f;          // its squared key norm (this lane's item)
   // Operands of tile t+1 (ring slot i1) come out of LDS while tile t is still being worked on,
   // into the registers tile t has just finished with: K (and the norms) once the last scores
   // of the tile are issued, V after its last P.V product.  They were published one tile ago
@@ -341,7 +348,7 @@ __device__ __forceinline__ void summarize_wave(const MfmaSummarizeParams& p, Sum
   auto read_k = [&](int i1) __attribute__((always_inline)) {
     k0.u = sm.kvbuf[i1][hl][0][0][lane];
     k1.u = sm.kvbuf[i1][hl][0][1][lane];
-    kn2 = sm.knorm[i1][hl][lane] + sm.knorm[i1][hl][lane ^ 32];
+    if constexpr (!SILU) kn2 = sm.knorm[i1][hl][lane] + sm.knorm[i1][hl][lane ^ 32];
   };
   auto read_v = [&](int i1) __attribute__((always_inline)) {
     v0.u = sm.kvbuf[i1][hl][1][0][lane];
@@ -368,7 +375,11 @@ __device__ __forceinline__ void summarize_wave(const MfmaSummarizeParams& p, Sum
       Pack8 p0, p1;
 #pragma unroll
       for (int i = 0; i < 16; i += 2) {
-        const float ea = __builtin_amdgcn_exp2f(sc[i]), eb = __builtin_amdgcn_exp2f(sc[i + 1]);
+        float ea = __builtin_amdgcn_exp2f(sc[i]), eb = __builtin_amdgcn_exp2f(sc[i + 1]);
+        if constexpr (SILU) {
+          ea = sc[i] * __builtin_amdgcn_rcpf(1.f + ea);
+          eb = sc[i + 1] * __builtin_amdgcn_rcpf(1.f + eb);
+        }
         const uint32_t pk = cvt_pk_bf16(ea, eb);
         if (i < 8) p0.w[i / 2] = pk; else p1.w[(i - 8) / 2] = pk;
       }
@@ -378,7 +389,7 @@ __device__ __forceinline__ void summarize_wave(const MfmaSummarizeParams& p, Sum
       // the bf16 weights the numerator uses.  It issues like one plain vector instruction
       // for four weights; two accumulators take turns so that consecutive products do not
       // wait for each other.
-      {
+      if constexpr (!SILU) {
         const i16x4 sel = __builtin_bit_cast(i16x4, onesrow[qb]);
 #pragma unroll
         for (int part = 0; part < 4; ++part) {
@@ -404,6 +415,28 @@ __device__ __forceinline__ void summarize_wave(const MfmaSummarizeParams& p, Sum
       l[qb] += lacc[0][qb] + lacc[1][qb];
       lacc[0][qb] = lacc[1][qb] = 0.f;
     }
+    if constexpr (SILU) {
+      // pointwise form: scores, weights (rows past the piece's end get weight 0), second product
+#pragma unroll
+      for (int qb = 0; qb < NQB; ++qb) {
+        f32x16 sc = {0};
+        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0.v, qop[qb][0], sc, 0, 0, 0);
+        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1.v, qop[qb][1], sc, 0, 0, 0);
+        Pack8 p0, p1;
+#pragma unroll
+        for (int i = 0; i < 16; i += 2) {
+          float wa = sc[i] * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(sc[i]));
+          float wb = sc[i + 1] * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(sc[i + 1]));
+          if (acc_row0(i) >= nvl) wa = 0.f;
+          if (acc_row0(i + 1) >= nvl) wb = 0.f;
+          const uint32_t pk = cvt_pk_bf16(wa, wb);
+          if (i < 8) p0.w[i / 2] = pk; else p1.w[(i - 8) / 2] = pk;
+        }
+        o[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v0.v, p0.v, o[qb], 0, 0, 0);
+        o[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v1.v, p1.v, o[qb], 0, 0, 0);
+      }
+      mode = 1;
+    } else {
     const bool general = mode == 2 || unsafe;
     if (mode != 2) {   // the reference so far: nothing (fresh piece) or the constant 0
 #pragma unroll
@@ -414,6 +447,7 @@ __device__ __forceinline__ void summarize_wave(const MfmaSummarizeParams& p, Sum
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb)
       attend_block(k0.v, k1.v, v0.v, v1.v, qop[qb][0], qop[qb][1], o[qb], l[qb], m[qb], general, masked, nvl);
+    }
     read_k(i1);
     read_v(i1);
     // the tile two ahead (past the end of the segment: a repeat of its last tile, never used)
@@ -500,7 +534,10 @@ __device__ __forceinline__ void summarize_wave(const MfmaSummarizeParams& p, Sum
   };
   // whether the tile whose operands are in registers is a plain one
   bool unsafe = unsafe_tile(kn2);
-  auto is_plain = [&]() __attribute__((always_inline)) { return !(ca.tiles_left == 1 || mode == 2 || unsafe); };
+  auto is_plain = [&]() __attribute__((always_inline)) {
+    if constexpr (SILU) return ca.tiles_left != 1;
+    return !(ca.tiles_left == 1 || mode == 2 || unsafe);
+  };
   bool plain = is_plain();
   for (;;) {
     while (__builtin_expect(plain, 1)) {
@@ -534,7 +571,7 @@ __device__ __forceinline__ void summarize_wave(const MfmaSummarizeParams& p, Sum
   }
 }
 
-template <int D, int NQB, int HPW>
+template <int D, int NQB, int HPW, int ATTN>
 __global__ __launch_bounds__(HPW * 128) void summarize_mfma_kernel(MfmaSummarizeParams p) {
   __shared__ SummarizeLds<D, HPW> sm;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform, kept scalar
@@ -553,9 +590,9 @@ __global__ __launch_bounds__(HPW * 128) void summarize_mfma_kernel(MfmaSummarize
   const int64_t seg_end = (seg_begin + p.seg < p.N) ? seg_begin + p.seg : p.N;
   // Both roles run the same sequence of barriers; only the MFMA operand order differs.
   if (wave & 1)
-    summarize_wave<D, NQB, HPW, 1>(p, sm, g, h, hl, 1, seg_begin, seg_end);
+    summarize_wave<D, NQB, HPW, 1, 2, ATTN>(p, sm, g, h, hl, 1, seg_begin, seg_end);
   else
-    summarize_wave<D, NQB, HPW, 0>(p, sm, g, h, hl, 0, seg_begin, seg_end);
+    summarize_wave<D, NQB, HPW, 0, 2, ATTN>(p, sm, g, h, hl, 0, seg_begin, seg_end);
 }
 
 // Four waves per head (two heads per workgroup): the K and V waves project as above, two more
@@ -563,7 +600,7 @@ __global__ __launch_bounds__(HPW * 128) void summarize_mfma_kernel(MfmaSummarize
 // wave at 4 query blocks, i.e. inside 256 vector registers and at two waves per SIMD.  Wave
 // w serves head w / 4 in slot (w + 2 (w / 4)) % 4, so that each SIMD (wave id mod 4) gets one
 // projecting and one attend-only wave.
-template <int D, int NQB>
+template <int D, int NQB, int ATTN>
 __global__ __launch_bounds__(512) void summarize_mfma4_kernel(MfmaSummarizeParams p) {
   constexpr int HPW = 2;
   __shared__ SummarizeLds<D, HPW> sm;
@@ -580,21 +617,28 @@ __global__ __launch_bounds__(512) void summarize_mfma4_kernel(MfmaSummarizeParam
   if (seg_begin >= p.N) return;          // padding blocks of the last group (whole workgroup)
   const int64_t seg_end = (seg_begin + p.seg < p.N) ? seg_begin + p.seg : p.N;
   if (slot == 0)
-    summarize_wave<D, NQB, HPW, 0, 4>(p, sm, g, h, hl, 0, seg_begin, seg_end);
+    summarize_wave<D, NQB, HPW, 0, 4, ATTN>(p, sm, g, h, hl, 0, seg_begin, seg_end);
   else if (slot == 1)
-    summarize_wave<D, NQB, HPW, 1, 4>(p, sm, g, h, hl, 1, seg_begin, seg_end);
+    summarize_wave<D, NQB, HPW, 1, 4, ATTN>(p, sm, g, h, hl, 1, seg_begin, seg_end);
   else
-    summarize_wave<D, NQB, HPW, 2, 4>(p, sm, g, h, hl, slot, seg_begin, seg_end);
+    summarize_wave<D, NQB, HPW, 2, 4, ATTN>(p, sm, g, h, hl, slot, seg_begin, seg_end);
 }
 
 // Merge of a user's partial records, ascending segment order (fixed, so the
-// result is bitwise reproducible): with m the running maximum of the m_c,
-// out = sum_c 2^(m_c - m) O_c / sum_c 2^(m_c - m) l_c.   One block per (user, head, query block), 256 threads: wave w
-// owns accumulator registers 4w..4w+3, i.e. channels 8w + 4 hf + 0..3.
+// result is bitwise reproducible).  Softmax form: with m the running maximum of the m_c,
+// out = sum_c 2^(m_c - m) O_c / sum_c 2^(m_c - m) l_c; the self term (Ks != null) is one more
+// record (m = own score, l = 1, O = own value), taken last.  SiLU form: out =
+// (-ln 2 sum_c O_c + SiLU(own score) own value) / L_b (the records hold sums of
+// t / (1 + 2^t) v with t = -s log2 e).  One block per (user, head, query block), 256 threads:
+// wave w owns accumulator registers 4w..4w+3, i.e. channels 8w + 4 hf + 0..3.
+template <bool SILU>
 __global__ __launch_bounds__(256) void merge_mfma_kernel(const float* __restrict__ partials,
                                                          const int64_t* __restrict__ offsets, int S, int d,
                                                          int H, int seg, int64_t G,
-                                                         uint16_t* __restrict__ out, int* status) {
+                                                         uint16_t* __restrict__ out, int* status,
+                                                         const uint16_t* __restrict__ Q, int64_t q_user_stride,
+                                                         const float* __restrict__ Ks,
+                                                         const float* __restrict__ Vs, float scale) {
   const int nqb = S / 32;
   const int qb = blockIdx.x % nqb, h = (blockIdx.x / nqb) % H, b = blockIdx.x / (nqb * H);
   // without a plan kernel in front (offsets checked on the host) the status word is cleared here
@@ -610,6 +654,19 @@ __global__ __launch_bounds__(256) void merge_mfma_kernel(const float* __restrict
   int64_t g0 = begin / seg, g1 = (end - 1) / seg;
   if (g0 < 0) g0 = 0;
   if (g1 > G - 1) g1 = G - 1;
+  // the query's own key and value (self term): score in the units of the records' m
+  float s_self = 0.f, vs[4] = {0.f, 0.f, 0.f, 0.f};
+  if (Ks) {
+    const int i = qb * 32 + l32;
+    const uint16_t* q = Q + q_user_stride * b + int64_t(i) * d + 32 * h;
+    const int64_t srow = (q_user_stride ? int64_t(b) * S : 0) + i;
+    const float* ks = Ks + srow * d + 32 * h;
+#pragma unroll 8
+    for (int c = 0; c < 32; ++c) s_self = fmaf(__uint_as_float(uint32_t(q[c]) << 16), ks[c], s_self);
+    s_self *= scale;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) vs[r] = Vs[srow * d + 32 * h + 8 * w + 4 * hf + r];
+  }
   auto rec = [&](int64_t g) __attribute__((always_inline)) { return partials + (((g + b) * H + h) * nqb + qb) * kRecFloats + lane; };
   // One pass with a running maximum (rescale when it moves); loads are issued kBatch
   // records at a time so a long user is not a chain of dependent round trips.
@@ -630,6 +687,14 @@ __global__ __launch_bounds__(256) void merge_mfma_kernel(const float* __restrict
     }
 #pragma unroll
     for (int u = 0; u < kBatch; ++u) {     // ascending segment order
+      if (SILU) {
+        const float on = g + u <= g1 ? 1.f : 0.f;
+        o0 = fmaf(v[u][2], on, o0);
+        o1 = fmaf(v[u][3], on, o1);
+        o2 = fmaf(v[u][4], on, o2);
+        o3 = fmaf(v[u][5], on, o3);
+        continue;
+      }
       const float mn = fmaxf(m, v[u][0]);
       const float keep = exp2f(m - mn);       // 0 on the first record (m = -inf), 1 while the maximum stands
       const float wgt = exp2f(v[u][0] - mn);  // 0 for the padding entries
@@ -641,7 +706,26 @@ __global__ __launch_bounds__(256) void merge_mfma_kernel(const float* __restrict
       m = mn;
     }
   }
-  const float inv = 1.f / l;
+  float inv;
+  if (SILU) {
+    inv = 1.f / float(end - begin);
+    const float wself = Ks ? s_self / (1.f + expf(-s_self)) : 0.f;
+    o0 = fmaf(o0, -0.69314718056f, wself * vs[0]);
+    o1 = fmaf(o1, -0.69314718056f, wself * vs[1]);
+    o2 = fmaf(o2, -0.69314718056f, wself * vs[2]);
+    o3 = fmaf(o3, -0.69314718056f, wself * vs[3]);
+  } else {
+    if (Ks) {
+      const float mn = fmaxf(m, s_self);
+      const float keep = exp2f(m - mn), wgt = exp2f(s_self - mn);
+      l = fmaf(l, keep, wgt);
+      o0 = fmaf(vs[0], wgt, o0 * keep);
+      o1 = fmaf(vs[1], wgt, o1 * keep);
+      o2 = fmaf(vs[2], wgt, o2 * keep);
+      o3 = fmaf(vs[3], wgt, o3 * keep);
+    }
+    inv = 1.f / l;
+  }
   uint2 pk;
   pk.x = uint32_t(f32_to_bf16_bits(o0 * inv)) | (uint32_t(f32_to_bf16_bits(o1 * inv)) << 16);
   pk.y = uint32_t(f32_to_bf16_bits(o2 * inv)) | (uint32_t(f32_to_bf16_bits(o3 * inv)) << 16);
@@ -654,7 +738,7 @@ static bool shape_d128(const vista_summarize_desc& d) { return d.d == 128 && d.H
 static bool shape_d256(const vista_summarize_desc& d) { return d.d == 256 && d.H == 8; }
 
 bool mfma_summarize_supported(const vista_summarize_desc& d) {
-  if (d.dtype != VISTA_BF16 || d.attn != VISTA_ATTN_SOFTMAX || d.flags != 0) return false;
+  if (d.dtype != VISTA_BF16 || d.attn == VISTA_ATTN_QLA) return false;
   if (!(shape_d128(d) || shape_d256(d))) return false;
   return d.S == 64 || d.S == 128 || d.S == 256 || d.S == 512;
 }
@@ -664,27 +748,50 @@ static size_t partial_bytes(const vista_summarize_desc& d, int seg) {
   return size_t(G + d.B) * d.H * (d.S / 32) * kRecFloats * sizeof(float);
 }
 
+// [header][seg_user][partial records][K' of the seeds][V' of the seeds]
 size_t mfma_summarize_workspace(const vista_summarize_desc& d, int seg) {
   const int64_t G = (d.total_items + seg - 1) / seg;
-  return kHeaderBytes + plan_bytes(G) + ((partial_bytes(d, seg) + 255) & ~size_t(255));
+  return kHeaderBytes + plan_bytes(G) + ((partial_bytes(d, seg) + 255) & ~size_t(255)) + 2 * self_kv_bytes(d);
 }
 
-template <int D, int NQB>
+template <int D, int NQB, int ATTN>
 static hipError_t launch_main4(const MfmaSummarizeParams& p, int64_t G, hipStream_t s) {
   const int64_t groups = (G + 7) / 8;
   const int64_t blocks = groups * 8 * p.nhg;
-  return launch(summarize_mfma4_kernel<D, NQB>, dim3(unsigned(blocks)), dim3(512), 0, s, p);
+  return launch(summarize_mfma4_kernel<D, NQB, ATTN>, dim3(unsigned(blocks)), dim3(512), 0, s, p);
 }
 
-template <int D, int NQB, int HPW>
+template <int D, int NQB, int HPW, int ATTN>
 static hipError_t launch_main(const MfmaSummarizeParams& p, int64_t G, hipStream_t s) {
   const int64_t groups = (G + 7) / 8;
   const int64_t blocks = groups * 8 * p.nhg;
-  return launch(summarize_mfma_kernel<D, NQB, HPW>, dim3(unsigned(blocks)), dim3(HPW * 128), 0, s, p);
+  return launch(summarize_mfma_kernel<D, NQB, HPW, ATTN>, dim3(unsigned(blocks)), dim3(HPW * 128), 0, s, p);
+}
+
+template <int ATTN>
+static hipError_t launch_for_shape(MfmaSummarizeParams& p, const vista_summarize_desc& d, int64_t G,
+                                   hipStream_t s) {
+  if (shape_d128(d)) {
+    p.nhg = 1;
+    switch (d.S) {
+      case 64: return launch_main<128, 1, 4, ATTN>(p, G, s);
+      case 128: return launch_main<128, 2, 4, ATTN>(p, G, s);
+      case 256: return launch_main<128, 4, 4, ATTN>(p, G, s);
+      default: p.nhg = 2; return launch_main4<128, 4, ATTN>(p, G, s);
+    }
+  }
+  p.nhg = 4;
+  switch (d.S) {
+    case 64: return launch_main<256, 1, 2, ATTN>(p, G, s);
+    case 128: return launch_main4<256, 1, ATTN>(p, G, s);
+    case 256: return launch_main4<256, 2, ATTN>(p, G, s);
+    default: return launch_main4<256, 4, ATTN>(p, G, s);
+  }
 }
 
 vista_status mfma_summarize(const SummarizeArgs& a) {
   const vista_summarize_desc& d = a.desc;
+  const bool silu = d.attn == VISTA_ATTN_SILU;
   MfmaSummarizeParams p;
   p.X = static_cast<const uint16_t*>(a.X);
   p.offsets = a.offsets;
@@ -700,36 +807,30 @@ vista_status mfma_summarize(const SummarizeArgs& a) {
   p.H = d.H;
   p.N = d.total_items;
   p.seg = a.seg;
-  p.c = a.scale_log2;
+  p.c = silu ? -a.scale_log2 : a.scale_log2;
+  float* Ks = nullptr;
+  float* Vs = nullptr;
+  if (d.flags & VISTA_FLAG_SELF_TERM) {
+    Ks = reinterpret_cast<float*>(reinterpret_cast<char*>(p.partials) + ((partial_bytes(d, a.seg) + 255) & ~size_t(255)));
+    Vs = Ks + self_kv_bytes(d) / sizeof(float);
+    if (launch_self_kv(d, a.Q, a.Wk, a.Wv, Ks, Vs, a.stream) != hipSuccess) return VISTA_ERR_HIP;
+  }
   const int64_t merge_blocks = int64_t(d.B) * d.H * (d.S / 32);
   if ((a.G + 7) / 8 * 8 * 4 > 0x7FFFFFFF || merge_blocks > 0x7FFFFFFF) return VISTA_ERR_UNSUPPORTED;
   if (a.G > 0) {
-    hipError_t e;
-    if (shape_d128(d)) {
-      p.nhg = 1;
-      switch (d.S) {
-        case 64: e = launch_main<128, 1, 4>(p, a.G, a.stream); break;
-        case 128: e = launch_main<128, 2, 4>(p, a.G, a.stream); break;
-        case 256: e = launch_main<128, 4, 4>(p, a.G, a.stream); break;
-        default:
-          p.nhg = 2;
-          e = launch_main4<128, 4>(p, a.G, a.stream);
-          break;
-      }
-    } else {
-      p.nhg = 4;
-      switch (d.S) {
-        case 64: e = launch_main<256, 1, 2>(p, a.G, a.stream); break;
-        case 128: e = launch_main4<256, 1>(p, a.G, a.stream); break;
-        case 256: e = launch_main4<256, 2>(p, a.G, a.stream); break;
-        default: e = launch_main4<256, 4>(p, a.G, a.stream); break;
-      }
-    }
+    const hipError_t e = silu ? launch_for_shape<VISTA_ATTN_SILU>(p, d, a.G, a.stream)
+                              : launch_for_shape<VISTA_ATTN_SOFTMAX>(p, d, a.G, a.stream);
     if (e != hipSuccess) return VISTA_ERR_HIP;
   }
-  VISTA_LAUNCH(merge_mfma_kernel, dim3(unsigned(merge_blocks)), dim3(256), 0, a.stream, p.partials, a.offsets, d.S,
-               d.d, d.H, a.seg, a.G, static_cast<uint16_t*>(a.out),
-               a.seg_user ? nullptr : reinterpret_cast<int*>(a.workspace));
+  int* status = a.seg_user ? nullptr : reinterpret_cast<int*>(a.workspace);
+  if (silu)
+    VISTA_LAUNCH(merge_mfma_kernel<true>, dim3(unsigned(merge_blocks)), dim3(256), 0, a.stream, p.partials, a.offsets,
+                 d.S, d.d, d.H, a.seg, a.G, static_cast<uint16_t*>(a.out), status, p.Q, d.q_user_stride, Ks, Vs,
+                 a.scale_plain);
+  else
+    VISTA_LAUNCH(merge_mfma_kernel<false>, dim3(unsigned(merge_blocks)), dim3(256), 0, a.stream, p.partials, a.offsets,
+                 d.S, d.d, d.H, a.seg, a.G, static_cast<uint16_t*>(a.out), status, p.Q, d.q_user_stride, Ks, Vs,
+                 a.scale_log2);
   return VISTA_OK;
 }
 

@@ -79,3 +79,52 @@ def test_stage2_self_term_plain_path(dtype):
     V.vista_target_attend(dev(T, dtype), dev(Y, dtype), out, H=2, self_term=True)
     torch.cuda.synchronize()
     assert_blocks_close(host64(out), O.target_attend(T, Y, 2, self_term=True), dtype, "stage 2 self term")
+
+
+# ------------------------------------------------------------------ bf16 MFMA path
+
+@pytest.mark.parametrize("d,H,S", [(128, 4, 256), (128, 4, 64), (128, 4, 512), (256, 8, 512), (256, 8, 128)])
+@pytest.mark.parametrize("seg", [0, 96])
+@pytest.mark.parametrize("self_term", [False, True])
+def test_mfma_silu_form(d, H, S, seg, self_term):
+    """SiLU score form on the matrix cores: jagged users incl. empty, one item, ragged tails."""
+    X, off, Q, Wk, Wv = problem(31, LENS, d, S, "bf16")
+    got = run("silu", X, off, Q, Wk, Wv, H, "bf16", self_term, segment_items=seg, offsets_host=torch.from_numpy(off))
+    want = O.summarize_silu(X, off, Q, Wk, Wv, H, self_term=self_term)
+    assert_blocks_close(got, want, "bf16", f"mfma silu d={d} S={S} seg={seg} self={self_term}")
+    assert np.all(got[1] == 0) and np.all(got[8] == 0)
+
+
+def test_mfma_silu_per_user_queries_scale_and_extreme_scores():
+    X, off, Q, Wk, Wv = problem(32, [700, 0, 33, 1300], 128, 256, "bf16", per_user=True)
+    got = run("silu", X, off, Q, Wk, Wv, 4, "bf16", segment_items=256, scale=0.2)
+    assert_blocks_close(got, O.summarize_silu(X, off, Q, Wk, Wv, 4, scale=0.2), "bf16", "mfma silu per-user, scale 0.2")
+    # scores of several hundred either way: SiLU(s) -> s or -> 0, 2^t overflows to inf on the way
+    X, off, Q, Wk, Wv = problem(33, [300, 77], 128, 64, "bf16", qscale=12.0)
+    got = run("silu", X, off, Q, Wk, Wv, 4, "bf16", segment_items=64)
+    assert_blocks_close(got, O.summarize_silu(X, off, Q, Wk, Wv, 4), "bf16", "mfma silu large scores")
+
+
+@pytest.mark.parametrize("d,H,S,per_user", [(128, 4, 256, False), (256, 8, 512, True)])
+def test_mfma_softmax_self_term(d, H, S, per_user):
+    X, off, Q, Wk, Wv = problem(34, LENS, d, S, "bf16", per_user)
+    got = run("softmax", X, off, Q, Wk, Wv, H, "bf16", True, segment_items=128)
+    want = O.summarize(X, off, Q, Wk, Wv, H, self_term=True)
+    assert_blocks_close(got, want, "bf16", "mfma softmax self term")
+    assert np.all(got[1] == 0)
+    # the term matters: without it the one-item user's summary is a different one
+    plain = O.summarize(X, off, Q, Wk, Wv, H)
+    assert np.abs(plain[2] - want[2]).max() > 0.05 * np.abs(want[2]).max()
+
+
+def test_silu_form_at_the_jagged_workload_shape():
+    """64 users, lognormal lengths, d=128, 4 heads, S=256 at full launch shape: every output."""
+    c = I.CONFIGS[2]
+    lens = I.lengths(c)
+    off = I.offsets_from_lengths(lens)
+    X = I.history(c, lens)
+    Q, Wk, Wv = I.virtual_queries(c), I.projection(c, "W_k"), I.projection(c, "W_v")
+    got = run("silu", X, off, Q, Wk, Wv, c.H, "bf16", offsets_host=torch.from_numpy(off))
+    want = O.summarize_silu(X, off, Q, Wk, Wv, c.H)
+    err = assert_blocks_close(got, want, "bf16", "silu form, jagged workload")
+    print(f"silu form, jagged workload: max block error {err:.2e}", flush=True)
