@@ -185,6 +185,9 @@ bool mfma_summarize_supported(const vista_summarize_desc& d);
 size_t mfma_summarize_workspace(const vista_summarize_desc& d, int seg);
 vista_status mfma_summarize(const SummarizeArgs& a);
 
+bool mfma_qla_supported(const vista_summarize_desc& d);
+vista_status mfma_qla_state(const SummarizeArgs& a, float* partials);
+
 vista_status generic_target_attend(const vista_attend_desc& d, float scale_log2, const void* cand,
                                    const void* summ, void* out, hipStream_t s);
 bool mfma_target_attend_supported(const vista_attend_desc& d);

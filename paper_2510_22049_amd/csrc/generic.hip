@@ -311,8 +311,8 @@ static size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
 
 size_t generic_summarize_workspace(const vista_summarize_desc& d, int seg) {
   const int64_t G = (d.total_items + seg - 1) / seg;
-  return kHeaderBytes + plan_bytes(G) + align256(generic_partials_bytes(d, seg)) +
-         2 * align256(size_t(d.total_items) * d.d * sizeof(float)) + 2 * self_kv_bytes(d);
+  const size_t kv = mfma_qla_supported(d) ? 0 : 2 * align256(size_t(d.total_items) * d.d * sizeof(float));
+  return kHeaderBytes + plan_bytes(G) + align256(generic_partials_bytes(d, seg)) + kv + 2 * self_kv_bytes(d);
 }
 
 template <typename T>
@@ -321,12 +321,13 @@ static vista_status generic_summarize_t(const SummarizeArgs& a) {
   const int64_t N = d.total_items;
   char* base = a.workspace + kHeaderBytes + plan_bytes(a.G);
   float* partials = reinterpret_cast<float*>(base);
+  const size_t kv_each = mfma_qla_supported(d) ? 0 : align256(size_t(N) * d.d * sizeof(float));
   float* K = reinterpret_cast<float*>(base + align256(generic_partials_bytes(d, a.seg)));
-  float* V = K + align256(size_t(N) * d.d * sizeof(float)) / sizeof(float);
+  float* V = K + kv_each / sizeof(float);
   float* Ks = nullptr;
   float* Vs = nullptr;
   if (d.flags & VISTA_FLAG_SELF_TERM) {
-    Ks = V + align256(size_t(N) * d.d * sizeof(float)) / sizeof(float);
+    Ks = V + kv_each / sizeof(float);
     Vs = Ks + self_kv_bytes(d) / sizeof(float);
     if (launch_self_kv(d, a.Q, a.Wk, a.Wv, Ks, Vs, a.stream) != hipSuccess) return VISTA_ERR_HIP;
   }
@@ -334,7 +335,11 @@ static vista_status generic_summarize_t(const SummarizeArgs& a) {
   const bool silu = d.attn == VISTA_ATTN_SILU, qla = d.attn == VISTA_ATTN_QLA;
   // the softmax form works in base-2 units; the pointwise forms take the score as it is
   const float score_scale = silu ? a.scale_plain : a.scale_log2;
-  if (N > 0) {
+  if (N > 0 && mfma_qla_supported(d)) {
+    // bf16, head width 32: the state records come from the matrix-core kernel (same layout)
+    const vista_status st = mfma_qla_state(a, partials);
+    if (st != VISTA_OK) return st;
+  } else if (N > 0) {
     int64_t total = N * d.d;
     int64_t blocks = (total + 255) / 256;
     if (blocks > 0x7FFFFFFF) return VISTA_ERR_UNSUPPORTED;

@@ -128,3 +128,29 @@ def test_silu_form_at_the_jagged_workload_shape():
     want = O.summarize_silu(X, off, Q, Wk, Wv, c.H)
     err = assert_blocks_close(got, want, "bf16", "silu form, jagged workload")
     print(f"silu form, jagged workload: max block error {err:.2e}", flush=True)
+
+
+@pytest.mark.parametrize("d,H,S,per_user", [(128, 4, 256, False), (128, 4, 40, True), (256, 8, 512, False), (256, 8, 64, True)])
+@pytest.mark.parametrize("seg", [0, 96])
+@pytest.mark.parametrize("self_term", [False, True])
+def test_mfma_qla(d, H, S, per_user, seg, self_term):
+    """Quasi-linear attention with the state streamed on the matrix cores (any S: the queries
+    only meet the d_h x d_h state in the finishing kernel)."""
+    X, off, Q, Wk, Wv = problem(41, LENS, d, S, "bf16", per_user)
+    got = run("qla", X, off, Q, Wk, Wv, H, "bf16", self_term, segment_items=seg, offsets_host=torch.from_numpy(off))
+    want = O.summarize_qla(X, off, Q, Wk, Wv, H, self_term=self_term)
+    assert_blocks_close(got, want, "bf16", f"mfma qla d={d} S={S} seg={seg} self={self_term}")
+    assert np.all(got[1] == 0) and np.all(got[8] == 0)
+
+
+def test_qla_at_the_jagged_workload_shape_and_bitwise_repeatable():
+    c = I.CONFIGS[2]
+    lens = I.lengths(c)
+    off = I.offsets_from_lengths(lens)
+    X = I.history(c, lens)
+    Q, Wk, Wv = I.virtual_queries(c), I.projection(c, "W_k"), I.projection(c, "W_v")
+    got = run("qla", X, off, Q, Wk, Wv, c.H, "bf16", offsets_host=torch.from_numpy(off))
+    want = O.summarize_qla(X, off, Q, Wk, Wv, c.H)
+    err = assert_blocks_close(got, want, "bf16", "qla, jagged workload")
+    print(f"qla, jagged workload: max block error {err:.2e}", flush=True)
+    assert np.array_equal(got, run("qla", X, off, Q, Wk, Wv, c.H, "bf16", offsets_host=torch.from_numpy(off)))
