@@ -100,10 +100,11 @@ typedef struct {
  * device, so results are bitwise reproducible.
  *
  * vista_summarize_segment_items: the segment size the call will use
- * (desc->segment_items, or the default derived from total_items alone: the
- * history is cut into 256 k equal segments, k the smallest count that keeps a
- * segment at or below 8192 items; at least 256 items); 0 if the descriptor is
- * invalid.
+ * (desc->segment_items, or the default derived from total_items and the
+ * attention form alone: the history is cut into 256 k equal segments, k the
+ * smallest count that keeps a segment at or below 8192 items -- 1024 k segments
+ * of at most 2048 items for VISTA_ATTN_QLA, whose workgroups are small; at
+ * least 256 items); 0 if the descriptor is invalid.
  */
 int32_t vista_summarize_segment_items(const vista_summarize_desc* desc);
 

@@ -250,46 +250,95 @@ __global__ void qla_state_kernel(const float* __restrict__ K, const float* __res
 }
 
 // out_h = SiLU(Q_h) SiLU(Z_h) with Z_h the ascending-order sum of the user's states;
-// the self term adds (SiLU(q) . SiLU(k')) v'.  grid (B, H), Z staged in LDS.
-template <typename T>
-__global__ void qla_finish_kernel(const float* __restrict__ partials, const int64_t* __restrict__ offsets, int S,
-                                  int d, int H, int seg, int64_t G, T* __restrict__ out, const T* __restrict__ Q,
-                                  int64_t q_user_stride, const float* __restrict__ Ks,
-                                  const float* __restrict__ Vs) {
-  __shared__ float z[kMaxDh * kMaxDh];
-  const int dh = d / H;
+// the self term adds (SiLU(q) . SiLU(k')) v'.  grid (B, H, runs of 64 queries), Z staged in LDS.
+// DH = the head width when it is known at compile time (32: the matrix-core shapes), else 0.
+template <typename T, int DH>
+__global__ __launch_bounds__(256) void qla_finish_kernel(const float* __restrict__ partials,
+                                                         const int64_t* __restrict__ offsets, int S, int d, int H,
+                                                         int seg, int64_t G, T* __restrict__ out,
+                                                         const T* __restrict__ Q, int64_t q_user_stride,
+                                                         const float* __restrict__ Ks,
+                                                         const float* __restrict__ Vs) {
+  constexpr int kW = DH ? DH : kMaxDh;          // register rows are sized for it
+  __shared__ float z[kW * kW];
+  const int dh = DH ? DH : d / H;
   const int b = blockIdx.x, h = blockIdx.y;
   const int64_t begin = offsets[b], end = offsets[b + 1];
   T* dst = out + int64_t(b) * S * d + h * dh;
   if (end <= begin) {
-    for (int e = threadIdx.x; e < S * dh; e += blockDim.x) store_as(dst + int64_t(e / dh) * d + (e % dh), 0.f);
+    if (blockIdx.z == 0)
+      for (int e = threadIdx.x; e < S * dh; e += blockDim.x) store_as(dst + int64_t(e / dh) * d + (e % dh), 0.f);
     return;
   }
   int64_t g0 = begin / seg, g1 = (end - 1) / seg;
   if (g0 < 0) g0 = 0;
   if (g1 > G - 1) g1 = G - 1;
-  for (int e = threadIdx.x; e < dh * dh; e += blockDim.x) {
-    float acc = 0.f;
-    for (int64_t g = g0; g <= g1; ++g) acc += partials[((g + b) * H + h) * dh * dh + e];
-    z[e] = acc / (1.f + expf(-acc));
+  // ascending-order sum of the user's records; a thread owns four neighbouring entries and keeps
+  // eight 16-byte loads in flight, so a long user is not a chain of dependent round trips
+  const int zz = dh * dh;
+  if (zz % 4 == 0) {
+    for (int e = 4 * threadIdx.x; e < zz; e += 4 * blockDim.x) {
+      float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+      for (int64_t g = g0; g <= g1; g += 8) {
+        float4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+          v[u] = g + u <= g1 ? *reinterpret_cast<const float4*>(partials + ((g + u + b) * H + h) * zz + e)
+                             : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          acc.x += v[u].x;
+          acc.y += v[u].y;
+          acc.z += v[u].z;
+          acc.w += v[u].w;
+        }
+      }
+      z[e] = acc.x / (1.f + expf(-acc.x));
+      z[e + 1] = acc.y / (1.f + expf(-acc.y));
+      z[e + 2] = acc.z / (1.f + expf(-acc.z));
+      z[e + 3] = acc.w / (1.f + expf(-acc.w));
+    }
+  } else {
+    for (int e = threadIdx.x; e < zz; e += blockDim.x) {
+      float acc = 0.f;
+      for (int64_t g = g0; g <= g1; ++g) acc += partials[((g + b) * H + h) * zz + e];
+      z[e] = acc / (1.f + expf(-acc));
+    }
   }
   __syncthreads();
   const int64_t srow0 = q_user_stride ? int64_t(b) * S : 0;
-  for (int e = threadIdx.x; e < S * dh; e += blockDim.x) {
-    const int i = e / dh, t = e % dh;
-    const T* q = Q + q_user_stride * b + int64_t(i) * d + h * dh;
-    float o = 0.f, dot = 0.f;
+  // A block takes a run of 64 queries: their activated rows go to LDS (coalesced reads), then
+  // one query per thread walks the channels in a rolled loop -- a row of the state per step,
+  // read as a broadcast -- with the 32 or 64 outputs in registers.
+  __shared__ float qs[64][kW + 1];
+  const int i0 = blockIdx.z * 64;
+  for (int e = threadIdx.x; e < 64 * dh; e += blockDim.x) {
+    const int r = e / dh, a = e % dh;
+    float qa = 0.f;
+    if (i0 + r < S) qa = to_f32(Q[q_user_stride * b + int64_t(i0 + r) * d + h * dh + a]);
+    qs[r][a] = qa / (1.f + expf(-qa));
+  }
+  __syncthreads();
+  const int i = i0 + threadIdx.x;
+  if (i < S && threadIdx.x < 64) {
+    float o[kW];
+#pragma unroll
+    for (int t = 0; t < kW; ++t) o[t] = 0.f;
+    float dot = 0.f;
+#pragma unroll 1
     for (int a = 0; a < dh; ++a) {
-      const float qa = to_f32(q[a]);
-      const float pa = qa / (1.f + expf(-qa));
-      o = fmaf(pa, z[a * dh + t], o);
+      const float pa = qs[threadIdx.x][a];
+#pragma unroll
+      for (int t = 0; t < kW; ++t)
+        if (t < dh) o[t] = fmaf(pa, z[a * dh + t], o[t]);
       if (Ks) {
         const float k = Ks[(srow0 + i) * d + h * dh + a];
         dot = fmaf(pa, k / (1.f + expf(-k)), dot);
       }
     }
-    if (Ks) o = fmaf(dot, Vs[(srow0 + i) * d + h * dh + t], o);
-    store_as(dst + int64_t(i) * d + t, o);
+#pragma unroll
+    for (int t = 0; t < kW; ++t)
+      if (t < dh) store_as(dst + int64_t(i) * d + t, Ks ? fmaf(dot, Vs[(srow0 + i) * d + h * dh + t], o[t]) : o[t]);
   }
 }
 
@@ -357,9 +406,12 @@ static vista_status generic_summarize_t(const SummarizeArgs& a) {
                    d.q_user_stride, a.offsets, d.B, d.S, d.d, d.H, score_scale, N, a.seg, a.seg_user, partials);
   }
   T* out = static_cast<T*>(a.out);
-  if (qla)
-    VISTA_LAUNCH(qla_finish_kernel<T>, dim3(d.B, d.H), dim3(256), 0, a.stream, partials, a.offsets, d.S, d.d, d.H,
-                 a.seg, a.G, out, Q, d.q_user_stride, Ks, Vs);
+  if (qla && d.d / d.H == 32)
+    VISTA_LAUNCH((qla_finish_kernel<T, 32>), dim3(d.B, d.H, (d.S + 63) / 64), dim3(256), 0, a.stream, partials, a.offsets, d.S, d.d,
+                 d.H, a.seg, a.G, out, Q, d.q_user_stride, Ks, Vs);
+  else if (qla)
+    VISTA_LAUNCH((qla_finish_kernel<T, 0>), dim3(d.B, d.H, (d.S + 63) / 64), dim3(256), 0, a.stream, partials, a.offsets, d.S, d.d,
+                 d.H, a.seg, a.G, out, Q, d.q_user_stride, Ks, Vs);
   else if (silu)
     VISTA_LAUNCH((merge_kernel<T, true>), dim3(d.B, d.H), dim3(256), 0, a.stream, partials, a.offsets, d.S, d.d,
                  d.H, a.seg, a.G, out, Q, d.q_user_stride, Ks, Vs, score_scale);

@@ -79,10 +79,6 @@ __global__ __launch_bounds__(D * 2, 2) void qla_state_mfma_kernel(QlaParams p) {
   const int lane = tid & 63;
   const int hf = lane >> 5, l32 = lane & 31;
   const int h = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int64_t g = blockIdx.x;
-  const int64_t seg_begin = g * p.seg;
-  if (seg_begin >= p.N) return;
-  const int64_t seg_end = (seg_begin + p.seg < p.N) ? seg_begin + p.seg : p.N;
 
   // Weights of this head as B operands: element j of slice ks is W[16 ks + 8 hf + j][32 h + l32].
   // The key weights carry -log2(e): the projection then yields t = -k log2(e) and
@@ -102,10 +98,15 @@ __global__ __launch_bounds__(D * 2, 2) void qla_state_mfma_kernel(QlaParams p) {
     __builtin_amdgcn_sched_barrier(0);     // one slice's loads at a time: they all land in registers of their own
   }
 
+  // A workgroup keeps its weights and takes segments blockIdx.x, blockIdx.x + gridDim.x, ...
+  // (records are indexed by segment, so the result does not depend on the grid).
+  for (int64_t g = blockIdx.x; g * p.seg < p.N; g += gridDim.x) {
+  const int64_t seg_begin = g * p.seg;
+  const int64_t seg_end = (seg_begin + p.seg < p.N) ? seg_begin + p.seg : p.N;
   TileCursor ca, cf;
   ca.init(p.offsets, p.B, p.seg_user ? __builtin_amdgcn_readfirstlane(p.seg_user[g]) : find_user(p.offsets, p.B, seg_begin),
           seg_begin, seg_end);
-  if (!ca.valid) return;                 // only with invalid offsets (whole workgroup)
+  if (!ca.valid) continue;               // only with invalid offsets (whole workgroup)
   cf = ca;
 
   const int wave = h;
@@ -214,6 +215,9 @@ __global__ __launch_bounds__(D * 2, 2) void qla_state_mfma_kernel(QlaParams p) {
     xb = xb == kRing - 1 ? 0 : xb + 1;
     if (!ca.valid) break;
   }
+  wait_vm(Int<0>{});                     // the requests that ran past the segment's end have landed:
+  lds_barrier();                         // the ring is free for the next segment
+  }
 }
 
 }  // namespace
@@ -236,11 +240,13 @@ vista_status mfma_qla_state(const SummarizeArgs& a, float* partials) {
   p.H = d.H;
   p.N = d.total_items;
   p.seg = a.seg;
-  if (a.G > 0x7FFFFFFF) return VISTA_ERR_UNSUPPORTED;
+  // three resident workgroups per compute unit at D = 128 (one at D = 256), each walking its share of the segments
+  const int64_t resident = d.d == 128 ? 768 : 256;
+  const unsigned blocks = unsigned(a.G < resident ? a.G : resident);
   if (d.d == 128)
-    VISTA_LAUNCH(qla_state_mfma_kernel<128>, dim3(unsigned(a.G)), dim3(256), 0, a.stream, p);
+    VISTA_LAUNCH(qla_state_mfma_kernel<128>, dim3(blocks), dim3(256), 0, a.stream, p);
   else
-    VISTA_LAUNCH(qla_state_mfma_kernel<256>, dim3(unsigned(a.G)), dim3(512), 0, a.stream, p);
+    VISTA_LAUNCH(qla_state_mfma_kernel<256>, dim3(blocks), dim3(512), 0, a.stream, p);
   return VISTA_OK;
 }
 

@@ -35,8 +35,12 @@ vista_status check_summarize_desc(const vista_summarize_desc* d) {
 int32_t resolve_segment(const vista_summarize_desc* d) {
   if (d->segment_items > 0) return d->segment_items;
   const int64_t N = d->total_items;
-  const int64_t k = (N + 256 * 8192 - 1) / (256 * 8192) > 0 ? (N + 256 * 8192 - 1) / (256 * 8192) : 1;
-  int64_t s = (N + 256 * k - 1) / (256 * k);
+  // quasi-linear attention: a workgroup is four or eight waves with little state, several fit a
+  // compute unit, so its history is cut four times finer
+  const int64_t units = d->attn == VISTA_ATTN_QLA ? 1024 : 256;
+  const int64_t cap = d->attn == VISTA_ATTN_QLA ? 2048 : 8192;
+  const int64_t k = (N + units * cap - 1) / (units * cap) > 0 ? (N + units * cap - 1) / (units * cap) : 1;
+  int64_t s = (N + units * k - 1) / (units * k);
   s = (s + 31) / 32 * 32;
   if (s < 256) s = 256;
   return int32_t(s);
