@@ -286,28 +286,34 @@ def qla_backward(Q, K, V, dO, H: int):
     return dQ, dK, dV
 
 
-def quantize_summaries(Y):
+def quantize_summaries(Y, H: int):
     """Cache codec (Sec. 3.1 says the summaries are quantized for the cache and dequantized
     on use, and gives no scheme; this is the build's): symmetric int8 with one scale per
-    summary token,
+    summary token and head (the head's d/H channels share it),
         amax = max_c |y_c|,  scale = amax / 127,  code_c = round_half_even(y_c * (127 / amax)),
     all in fp32 (the decision that produces an integer is taken in the precision the
-    library takes it in).  A zero token gets scale 0 and zero codes.
-    Y [..., d] -> (codes int8 [..., d], scales float32 [...])."""
+    library takes it in).  An all-zero group gets scale 0 and zero codes.
+    Y [..., d] -> (codes int8 [..., d], scales float32 [..., H])."""
     y = np.asarray(Y, dtype=np.float32)
-    amax = np.abs(y).max(axis=-1)
+    d = y.shape[-1]
+    g = y.reshape(y.shape[:-1] + (H, d // H))
+    amax = np.abs(g).max(axis=-1)
     safe = np.where(amax > 0, amax, np.float32(1)).astype(np.float32)
     inv = (np.float32(127) / safe).astype(np.float32)
-    codes = np.rint((y * inv[..., None]).astype(np.float32))
+    codes = np.rint((g * inv[..., None]).astype(np.float32))
     codes = np.clip(codes, -127, 127).astype(np.int8)
     codes[amax == 0] = 0
     scales = np.where(amax > 0, (amax / np.float32(127)).astype(np.float32), np.float32(0)).astype(np.float32)
-    return codes, scales
+    return codes.reshape(y.shape), scales
 
 
 def dequantize_summaries(codes, scales) -> np.ndarray:
-    """y_c = code_c * scale (exact in fp64: an 8-bit integer times an fp32 number)."""
-    return np.asarray(codes, dtype=F64) * np.asarray(scales, dtype=F64)[..., None]
+    """y_c = code_c * scale of its (token, head) (exact in fp64: an 8-bit integer times an fp32 number)."""
+    c = np.asarray(codes, dtype=F64)
+    sc = np.asarray(scales, dtype=F64)
+    H = sc.shape[-1]
+    g = c.reshape(c.shape[:-1] + (H, c.shape[-1] // H)) * sc[..., None]
+    return g.reshape(c.shape)
 
 
 def sglu_ffn(y, W_g, W_u, W_o, eps: float = 1e-6) -> np.ndarray:

@@ -258,28 +258,34 @@ def test_target_attend_self_term():
 
 def test_codec_brute_force_and_rounding():
     g = np.random.default_rng(31)
-    Y = g.normal(size=(3, 4, 16)).astype(np.float32)
-    Y[1, 2] = 0.0
+    H, dh = 2, 8
+    Y = g.normal(size=(3, 4, H * dh)).astype(np.float32)
+    Y[1, 2, :dh] = 0.0                               # an all-zero (token, head) group
     Y[0, 0, :4] = [127.0, 0.5, 1.5, -2.5]            # amax = 127: scale 1, halves round to even
-    Y[0, 0, 4:] = 0.25
-    codes, scales = O.quantize_summaries(Y)
+    Y[0, 0, 4:dh] = 0.25
+    codes, scales = O.quantize_summaries(Y, H)
     assert codes.dtype == np.int8 and scales.dtype == np.float32
-    assert list(codes[0, 0, :4]) == [127, 0, 2, -2] and scales[0, 0] == 1.0
-    assert np.all(codes[1, 2] == 0) and scales[1, 2] == 0.0
-    for idx in np.ndindex(3, 4):
-        row = Y[idx]
-        amax = np.float32(np.abs(row).max())
+    assert codes.shape == Y.shape and scales.shape == (3, 4, H)
+    assert list(codes[0, 0, :4]) == [127, 0, 2, -2] and scales[0, 0, 0] == 1.0
+    assert np.all(codes[1, 2, :dh] == 0) and scales[1, 2, 0] == 0.0 and scales[1, 2, 1] > 0
+    for idx in np.ndindex(3, 4, H):
+        grp = Y[idx[0], idx[1], idx[2] * dh:(idx[2] + 1) * dh]
+        amax = np.float32(np.abs(grp).max())
         if amax == 0:
             continue
         inv = np.float32(127) / amax
-        want = [int(np.rint(np.float32(v * inv))) for v in row]
-        assert list(codes[idx]) == want
+        want = [int(np.rint(np.float32(v * inv))) for v in grp]
+        assert list(codes[idx[0], idx[1], idx[2] * dh:(idx[2] + 1) * dh]) == want
         assert scales[idx] == np.float32(amax / np.float32(127))
-        assert np.abs(codes[idx]).max() == 127
+        assert np.abs(want).max() == 127
     deq = O.dequantize_summaries(codes, scales)
-    assert np.all(np.abs(deq - Y) <= scales[..., None] * 0.5000001 + 1e-12)
-    again, scales2 = O.quantize_summaries(deq)        # a fixed point of the codec
+    step = np.repeat(scales, dh, axis=-1)
+    assert np.all(np.abs(deq - Y) <= step * 0.5000001 + 1e-12)
+    again, _ = O.quantize_summaries(deq, H)          # a fixed point of the codec
     assert np.array_equal(again, codes)
+    # one head: the whole row shares the scale
+    c1, s1 = O.quantize_summaries(Y, 1)
+    assert s1.shape == (3, 4, 1) and np.all(np.abs(c1).max(axis=-1) == 127)
 
 
 # ------------------------------------------------------------------ gradients of QLA
