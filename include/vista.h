@@ -234,6 +234,62 @@ vista_status vista_target_attend(const vista_attend_desc* desc,
                                  void* out,
                                  void* hip_stream);
 
+/* ------------------------------------------------ cache codec (int8) */
+
+/*
+ * Sec. 3.1: the summaries are quantized when they are written to the cache and
+ * dequantized when stage 2 reads them.  The paper fixes no scheme; this library's is
+ * symmetric int8 with one fp32 scale per (summary token, head):
+ *     amax = max |y_c| over the head's d/H channels,  scale = amax / 127,
+ *     code_c = round-half-even(y_c * (127 / amax)),    y_c ~ code_c * scale,
+ * every step in fp32; an all-zero group has scale 0 and zero codes.
+ *   codes   int8  [B, S, d]      scales  float [B, S, H]
+ * It halves the bytes stage 2 reads per user (S*d + 4*S*H instead of 2*S*d).
+ */
+typedef struct {
+  int64_t rows;   /* B * S summary tokens          */
+  int32_t d;      /* model width                   */
+  int32_t H;      /* heads (scale groups per row)  */
+  int32_t dtype;  /* dtype of y                    */
+} vista_codec_desc;
+
+/* y device [rows, d] dtype -> codes device int8 [rows, d], scales device float [rows, H].
+ * Supported: d/H <= 64.  No workspace. */
+vista_status vista_quantize_summaries(const vista_codec_desc* desc, const void* y, int8_t* codes, float* scales,
+                                      void* hip_stream);
+
+/*
+ * vista_summarize with the codec fused into its last kernel: the normalised fp32 summaries
+ * are quantized as they are produced and never stored in dtype.  Arguments as vista_summarize,
+ * with out_codes (device int8 [B, S, d]) and out_scales (device float [B, S, H]) in place of out.
+ * Supported: the shapes of the bf16 MFMA path, softmax and SiLU forms (else VISTA_ERR_UNSUPPORTED:
+ * run vista_summarize, then vista_quantize_summaries).
+ */
+vista_status vista_summarize_q8(const vista_summarize_desc* desc,
+                                const void* history_emb,
+                                const int64_t* offsets,
+                                const int64_t* offsets_host,
+                                const void* virtual_queries,
+                                const void* W_k,
+                                const void* W_v,
+                                int8_t* out_codes,
+                                float* out_scales,
+                                void* workspace, size_t workspace_bytes,
+                                void* hip_stream);
+
+/*
+ * vista_target_attend on quantized summaries: keys and values are code * scale, formed on
+ * the fly (the bf16 MFMA path rounds them to bf16 once, as it rounds every operand).
+ * candidates / out device [B, C, d] dtype; codes device int8 [B, S, d]; scales device float [B, S, H].
+ * Same supported set as vista_target_attend.
+ */
+vista_status vista_target_attend_q8(const vista_attend_desc* desc,
+                                    const void* candidates,
+                                    const int8_t* codes,
+                                    const float* scales,
+                                    void* out,
+                                    void* hip_stream);
+
 /* ------------------------------------------------ block between layers */
 
 typedef struct {

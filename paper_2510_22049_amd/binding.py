@@ -33,6 +33,9 @@ EXPORTS = (
     "vista_summarize",
     "vista_summarize_static",
     "vista_target_attend",
+    "vista_target_attend_q8",
+    "vista_quantize_summaries",
+    "vista_summarize_q8",
     "vista_sglu_ffn",
 )
 
@@ -47,6 +50,10 @@ class SummarizeDesc(C.Structure):
 class AttendDesc(C.Structure):
     _fields_ = [("B", C.c_int32), ("C", C.c_int32), ("S", C.c_int32), ("d", C.c_int32),
                 ("H", C.c_int32), ("dtype", C.c_int32), ("scale", C.c_float), ("flags", C.c_int32)]
+
+
+class CodecDesc(C.Structure):
+    _fields_ = [("rows", C.c_int64), ("d", C.c_int32), ("H", C.c_int32), ("dtype", C.c_int32)]
 
 
 class FfnDesc(C.Structure):
@@ -86,6 +93,12 @@ def lib() -> C.CDLL:
     L.vista_summarize.argtypes = [C.POINTER(SummarizeDesc), vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
     L.vista_summarize_static.restype = C.c_int
     L.vista_summarize_static.argtypes = [C.POINTER(SummarizeDesc), vp, vp, vp, vp, vp, vp, vp, vp]
+    L.vista_summarize_q8.restype = C.c_int
+    L.vista_summarize_q8.argtypes = [C.POINTER(SummarizeDesc), vp, vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+    L.vista_quantize_summaries.restype = C.c_int
+    L.vista_quantize_summaries.argtypes = [C.POINTER(CodecDesc), vp, vp, vp, vp]
+    L.vista_target_attend_q8.restype = C.c_int
+    L.vista_target_attend_q8.argtypes = [C.POINTER(AttendDesc), vp, vp, vp, vp, vp]
     L.vista_target_attend.restype = C.c_int
     L.vista_target_attend.argtypes = [C.POINTER(AttendDesc), vp, vp, vp, vp]
     L.vista_sglu_ffn.restype = C.c_int
@@ -174,6 +187,56 @@ def vista_summarize(history_emb, offsets, virtual_queries, W_k, W_v, out, *, H, 
     if st != VISTA_OK:
         raise VistaError(st)
     return workspace
+
+
+def vista_summarize_q8(history_emb, offsets, virtual_queries, W_k, W_v, out_codes, out_scales, *, H, scale=0.0,
+                       segment_items=0, offsets_host=None, workspace=None, attn=VISTA_ATTN_SOFTMAX, self_term=False):
+    """Stage 1 with the cache codec fused: out_codes int8 [B,S,d], out_scales float32 [B,S,H]."""
+    B = offsets.numel() - 1
+    S, d = virtual_queries.shape[-2:]
+    N = history_emb.shape[0]
+    desc = summarize_desc(B, S, d, H, _dtype_code(history_emb), N, virtual_queries.dim() == 3, scale,
+                          segment_items, attn, self_term)
+    need = vista_summarize_workspace_bytes(desc)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=history_emb.device)
+    if out_codes.dtype != torch.int8 or out_scales.dtype != torch.float32:
+        raise TypeError("out_codes must be int8 and out_scales float32")
+    host = offsets_host.contiguous().data_ptr() if offsets_host is not None else None
+    st = lib().vista_summarize_q8(C.byref(desc), _dev(history_emb, "history_emb") if N else None,
+                                  _dev(offsets, "offsets"), host, _dev(virtual_queries, "virtual_queries"),
+                                  _dev(W_k, "W_k"), _dev(W_v, "W_v"), _dev(out_codes, "out_codes"),
+                                  _dev(out_scales, "out_scales"), _dev(workspace, "workspace"), workspace.numel(),
+                                  _stream())
+    if st != VISTA_OK:
+        raise VistaError(st)
+    return workspace
+
+
+def vista_quantize_summaries(y, codes, scales, *, H):
+    """Cache codec: y [..., d] -> codes int8 [..., d], scales float32 [..., H] (device tensors)."""
+    d = y.shape[-1]
+    desc = CodecDesc(rows=y.numel() // d, d=d, H=H, dtype=_dtype_code(y))
+    if codes.dtype != torch.int8 or scales.dtype != torch.float32:
+        raise TypeError("codes must be int8 and scales float32")
+    st = lib().vista_quantize_summaries(C.byref(desc), _dev(y, "y"), _dev(codes, "codes"), _dev(scales, "scales"),
+                                        _stream())
+    if st != VISTA_OK:
+        raise VistaError(st)
+
+
+def vista_target_attend_q8(candidates, codes, scales, out, *, H, scale=0.0, self_term=False):
+    """Stage 2 on quantized summaries: codes int8 [B,S,d], scales float32 [B,S,H]."""
+    B, Cn, d = candidates.shape
+    S = codes.shape[1]
+    desc = AttendDesc(B=B, C=Cn, S=S, d=d, H=H, dtype=_dtype_code(candidates), scale=scale,
+                      flags=VISTA_FLAG_SELF_TERM if self_term else 0)
+    if codes.dtype != torch.int8 or scales.dtype != torch.float32:
+        raise TypeError("codes must be int8 and scales float32")
+    st = lib().vista_target_attend_q8(C.byref(desc), _dev(candidates, "candidates"), _dev(codes, "codes"),
+                                      _dev(scales, "scales"), _dev(out, "out"), _stream())
+    if st != VISTA_OK:
+        raise VistaError(st)
 
 
 def vista_summarize_static(history_emb, offsets, virtual_queries, W_k, W_v, out, *, H, scale=0.0,

@@ -44,7 +44,10 @@ constexpr int kRound = 64;                 // candidates per round
 
 struct AttendParams {
   const uint16_t* cand;
-  const uint16_t* summ;
+  const uint16_t* summ;     // bf16 summaries, or null when they come as codes
+  const int8_t* codes;      // int8 summaries [B, S, d] ...
+  const float* scales;      // ... and their scales [B, S, H]
+  int self_term;            // candidates also attend to themselves (Eq. 3)
   uint16_t* out;
   int B, C, S, d, H;
   int rounds_per_wg;  // rounds (of 64 candidates) a workgroup takes
@@ -171,12 +174,39 @@ __global__ __launch_bounds__(kThreads, (NKB <= 6 || NKB == 8) ? 3 : 2) void atte
   };
 
   // ---- the slab of summaries and the first candidate tile are requested together
+  if (p.codes == nullptr) {
 #pragma unroll
-  for (int i = 0; i < NKB; ++i) {
-    const int j = (i * kWaves + wave) * 64 + lane;    // slab chunk: row j / 8
-    const int row = j / kRowChunks;                   // < 32 NKB = S
-    dma(&sm.slab[(i * kWaves + wave) * 64], Yb,
-        uint32_t(row) * uint32_t(row_bytes) + uint32_t(((j & (kRowChunks - 1)) ^ ((row >> 1) & (kRowChunks - 1))) * 16));
+    for (int i = 0; i < NKB; ++i) {
+      const int j = (i * kWaves + wave) * 64 + lane;    // slab chunk: row j / 8
+      const int row = j / kRowChunks;                   // < 32 NKB = S
+      dma(&sm.slab[(i * kWaves + wave) * 64], Yb,
+          uint32_t(row) * uint32_t(row_bytes) + uint32_t(((j & (kRowChunks - 1)) ^ ((row >> 1) & (kRowChunks - 1))) * 16));
+    }
+  } else {
+    // Quantized summaries (Sec. 3.1): 16 codes of a row at a time are turned into code * scale,
+    // rounded to bf16 and put where the raw rows would have landed.  A thread takes quarter
+    // q of the two heads' 64 codes of a row; its scale is that of head q / 2.
+    const int8_t* Cb = p.codes + int64_t(b) * p.S * p.d + hg * (32 * kHeads);
+    const float* Sb = p.scales + int64_t(b) * p.S * p.H + hg * kHeads;
+    for (int j = tid; j < NKB * 32 * 4; j += kThreads) {
+      const int row = j >> 2, q = j & 3;
+      const uint4 raw = *reinterpret_cast<const uint4*>(Cb + int64_t(row) * p.d + 16 * q);
+      const float sc = Sb[int64_t(row) * p.H + (q >> 1)];
+      // code + 128 is an unsigned byte (flip the sign bit); it converts exactly and
+      // (byte - 128) * scale is one fused multiply-add
+      const uint32_t w[4] = {raw.x ^ 0x80808080u, raw.y ^ 0x80808080u, raw.z ^ 0x80808080u, raw.w ^ 0x80808080u};
+      const float off = -128.f * sc;
+      uint32_t pk[8];
+#pragma unroll
+      for (int e = 0; e < 16; e += 2) {
+        const float a = fmaf(float((w[e / 4] >> (8 * (e % 4))) & 0xFFu), sc, off);
+        const float c2 = fmaf(float((w[e / 4] >> (8 * (e % 4) + 8)) & 0xFFu), sc, off);
+        pk[e / 2] = cvt_pk_bf16(a, c2);
+      }
+      const int sw = (row >> 1) & (kRowChunks - 1);
+      sm.slab[row * kRowChunks + ((2 * q) ^ sw)] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+      sm.slab[row * kRowChunks + ((2 * q + 1) ^ sw)] = make_uint4(pk[4], pk[5], pk[6], pk[7]);
+    }
   }
   // the first NB-1 rounds' parts (a round past the end repeats the last one: the count of
   // loads in flight stays a constant)
@@ -292,7 +322,9 @@ __global__ __launch_bounds__(kThreads, (NKB <= 6 || NKB == 8) ? 3 : 2) void atte
       qn2 = __builtin_amdgcn_fdot2_f32_bf16(b2, b2, qn2, false);
     }
     qn2 += __shfl_xor(qn2, 32, 64);
-    const bool general = __builtin_amdgcn_ballot_w64(qn2 * kmax2 > kSafeBound2) != 0;
+    // (with the self term the candidate's own score c |q|^2 must stay in range as well)
+    const bool general = __builtin_amdgcn_ballot_w64(qn2 * kmax2 > kSafeBound2 || (p.self_term && qn2 * p.c > 60.f)) != 0;
+    float mrun = 0.f;          // reference maximum the weights were taken against
     // Key blocks stream through: 32 keys x 32 candidates of scores at a time.  The common
     // route is straight-line code over all key blocks (one scheduling region), the scores
     // of a block computed while the previous block's exponentials run.
@@ -376,6 +408,31 @@ __global__ __launch_bounds__(kThreads, (NKB <= 6 || NKB == 8) ? 3 : 2) void atte
       }
       lsum = (l[0] + l[1]) + (l[2] + l[3]);
       lsum += __shfl_xor(lsum, 32, 64);
+      mrun = m;
+    }
+    if (p.self_term) {
+      // one more key and value: the candidate itself (no projections in this stage), score c |q|^2
+      const float s_self = p.c * qn2;
+      float ps;
+      if (general) {
+        const float mn = fmaxf(mrun, s_self);
+        const float alpha = __builtin_amdgcn_exp2f(mrun - mn);
+        lsum *= alpha;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[i] *= alpha;
+        ps = __builtin_amdgcn_exp2f(s_self - mn);
+      } else {
+        ps = __builtin_amdgcn_exp2f(s_self);
+      }
+      lsum += ps;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const uint2 own = reinterpret_cast<const uint2*>(&sm.part[wave][cur][l32 * 4 + (g ^ osw)])[hf];
+        o[4 * g] = fmaf(ps, bf16_lo(own.x), o[4 * g]);
+        o[4 * g + 1] = fmaf(ps, bf16_hi(own.x), o[4 * g + 1]);
+        o[4 * g + 2] = fmaf(ps, bf16_lo(own.y), o[4 * g + 2]);
+        o[4 * g + 3] = fmaf(ps, bf16_hi(own.y), o[4 * g + 3]);
+      }
     }
     const float inv = __builtin_amdgcn_rcpf(lsum);
     // register group g holds channels 8 g + 4 hf + 0..3 of the head: 8 bytes at chunk 4 hl + g, half hf.
@@ -403,15 +460,19 @@ hipError_t launch_attend(const AttendParams& p, hipStream_t s) {
 }  // namespace
 
 bool mfma_target_attend_supported(const vista_attend_desc& d) {
-  return d.dtype == VISTA_BF16 && d.flags == 0 && d.d == 32 * d.H && d.H % kHeads == 0 && d.S % 32 == 0 && (d.S <= 256 || (d.S % 64 == 0 && d.S <= 512)) &&
+  return d.dtype == VISTA_BF16 && d.d == 32 * d.H && d.H % kHeads == 0 && d.S % 32 == 0 && (d.S <= 256 || (d.S % 64 == 0 && d.S <= 512)) &&
          int64_t(d.C) * d.d * 2 < (int64_t(1) << 32);
 }
 
 vista_status mfma_target_attend(const vista_attend_desc& d, float scale_log2, const void* cand,
-                                const void* summ, void* out, hipStream_t s) {
+                                const void* summ, const int8_t* codes, const float* scales, void* out,
+                                hipStream_t s) {
   AttendParams p;
   p.cand = static_cast<const uint16_t*>(cand);
   p.summ = static_cast<const uint16_t*>(summ);
+  p.codes = codes;
+  p.scales = scales;
+  p.self_term = (d.flags & VISTA_FLAG_SELF_TERM) ? 1 : 0;
   p.out = static_cast<uint16_t*>(out);
   p.B = d.B; p.C = d.C; p.S = d.S; p.d = d.d; p.H = d.H;
   p.c = scale_log2;

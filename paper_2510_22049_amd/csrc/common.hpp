@@ -172,6 +172,7 @@ struct SummarizeArgs {
   const void* Wk;
   const void* Wv;
   void* out;
+  float* out_scales;  // non-null: out receives int8 codes and this their scales [B, S, H] (cache codec)
   char* workspace;
   hipStream_t stream;
 };
@@ -188,11 +189,15 @@ vista_status mfma_summarize(const SummarizeArgs& a);
 bool mfma_qla_supported(const vista_summarize_desc& d);
 vista_status mfma_qla_state(const SummarizeArgs& a, float* partials);
 
+// summaries either as `summ` (dtype) or, when codes != null, as int8 codes with fp32 scales [B, S, H]
 vista_status generic_target_attend(const vista_attend_desc& d, float scale_log2, const void* cand,
-                                   const void* summ, void* out, hipStream_t s);
+                                   const void* summ, const int8_t* codes, const float* scales, void* out,
+                                   hipStream_t s);
+vista_status generic_quantize(const vista_codec_desc& d, const void* y, int8_t* codes, float* scales, hipStream_t s);
 bool mfma_target_attend_supported(const vista_attend_desc& d);
 vista_status mfma_target_attend(const vista_attend_desc& d, float scale_log2, const void* cand,
-                                const void* summ, void* out, hipStream_t s);
+                                const void* summ, const int8_t* codes, const float* scales, void* out,
+                                hipStream_t s);
 
 vista_status generic_sglu_ffn(const vista_ffn_desc& d, float eps, const void* y, const void* Wg,
                               const void* Wu, const void* Wo, void* out, hipStream_t s);

@@ -428,8 +428,10 @@ vista_status generic_summarize(const SummarizeArgs& a) {
 
 // ------------------------------------------------------------------ stage 2
 // One thread per (user, candidate, head); keys = values = the user's summaries.
+// Summaries come as `summ` or, when codes != null, as int8 codes times the scale of their (token, head).
 template <typename T>
 __global__ void target_attend_kernel(const T* __restrict__ cand, const T* __restrict__ summ,
+                                     const int8_t* __restrict__ codes, const float* __restrict__ scales,
                                      T* __restrict__ out, int64_t total, int C, int S, int d, int H,
                                      float scale_log2, int self_term) {
   const int dh = d / H;
@@ -439,7 +441,8 @@ __global__ void target_attend_kernel(const T* __restrict__ cand, const T* __rest
   const int64_t bc = idx / H;     // flat (user, candidate)
   const int64_t b = bc / C;
   const T* qrow = cand + bc * d + h * dh;
-  const T* Y = summ + b * S * d + h * dh;
+  const T* Y = codes ? nullptr : summ + b * S * d + h * dh;
+  const int8_t* Yq = codes ? codes + b * S * d + h * dh : nullptr;
   float q[kMaxDh], o[kMaxDh];
   for (int t = 0; t < kMaxDh; ++t) {
     q[t] = t < dh ? to_f32(qrow[t]) * scale_log2 : 0.f;
@@ -448,16 +451,25 @@ __global__ void target_attend_kernel(const T* __restrict__ cand, const T* __rest
   float m = -INFINITY, l = 0.f;
   // with the self term the candidate's own embedding is one more key and value (Eq. 3)
   for (int j = 0; j < S + (self_term ? 1 : 0); ++j) {
-    const T* y = j < S ? Y + int64_t(j) * d : qrow;
+    float y[kMaxDh];
+    if (j < S && codes) {
+      const float sc = scales[(b * S + j) * H + h];
+      for (int t = 0; t < kMaxDh; ++t)
+        if (t < dh) y[t] = float(Yq[int64_t(j) * d + t]) * sc;
+    } else {
+      const T* src = j < S ? Y + int64_t(j) * d : qrow;
+      for (int t = 0; t < kMaxDh; ++t)
+        if (t < dh) y[t] = to_f32(src[t]);
+    }
     float s = 0.f;
     for (int t = 0; t < kMaxDh; ++t)
-      if (t < dh) s = fmaf(q[t], to_f32(y[t]), s);
+      if (t < dh) s = fmaf(q[t], y[t], s);
     float mn = fmaxf(m, s);
     float alpha = exp2f(m - mn);
     float p = exp2f(s - mn);
     l = l * alpha + p;
     for (int t = 0; t < kMaxDh; ++t)
-      if (t < dh) o[t] = fmaf(o[t], alpha, p * to_f32(y[t]));
+      if (t < dh) o[t] = fmaf(o[t], alpha, p * y[t]);
     m = mn;
   }
   T* dst = out + bc * d + h * dh;
@@ -467,21 +479,61 @@ __global__ void target_attend_kernel(const T* __restrict__ cand, const T* __rest
 }
 
 vista_status generic_target_attend(const vista_attend_desc& d, float scale_log2, const void* cand,
-                                   const void* summ, void* out, hipStream_t s) {
+                                   const void* summ, const int8_t* codes, const float* scales, void* out,
+                                   hipStream_t s) {
   if (d.d / d.H > kMaxDh) return VISTA_ERR_UNSUPPORTED;
   int64_t total = int64_t(d.B) * d.C * d.H;
   int64_t blocks = (total + 127) / 128;
   if (blocks > 0x7FFFFFFF) return VISTA_ERR_UNSUPPORTED;
   if (d.dtype == VISTA_BF16)
     VISTA_LAUNCH(target_attend_kernel<bf16_t>, dim3(unsigned(blocks)), dim3(128), 0, s,
-                       static_cast<const bf16_t*>(cand), static_cast<const bf16_t*>(summ),
+                       static_cast<const bf16_t*>(cand), static_cast<const bf16_t*>(summ), codes, scales,
                        static_cast<bf16_t*>(out), total, d.C, d.S, d.d, d.H, scale_log2,
                        int(d.flags & VISTA_FLAG_SELF_TERM));
   else
     VISTA_LAUNCH(target_attend_kernel<float>, dim3(unsigned(blocks)), dim3(128), 0, s,
-                       static_cast<const float*>(cand), static_cast<const float*>(summ),
+                       static_cast<const float*>(cand), static_cast<const float*>(summ), codes, scales,
                        static_cast<float*>(out), total, d.C, d.S, d.d, d.H, scale_log2,
                        int(d.flags & VISTA_FLAG_SELF_TERM));
+  return VISTA_OK;
+}
+
+// ------------------------------------------------------- cache codec
+// One thread per (token, head): amax over the head's channels, scale = amax / 127,
+// code = round-half-even(y * (127 / amax)); every step in fp32 (Sec. 3.1 names the step,
+// the scheme is this library's).
+template <typename T>
+__global__ void quantize_kernel(const T* __restrict__ y, int8_t* __restrict__ codes, float* __restrict__ scales,
+                                int64_t groups, int d, int H) {
+  const int64_t gidx = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (gidx >= groups) return;
+  const int dh = d / H;
+  const int64_t row = gidx / H;
+  const int h = int(gidx - row * H);
+  const T* src = y + row * d + h * dh;
+  float v[kMaxDh];
+  float amax = 0.f;
+  for (int t = 0; t < kMaxDh; ++t) {
+    v[t] = t < dh ? to_f32(src[t]) : 0.f;
+    amax = fmaxf(amax, fabsf(v[t]));
+  }
+  const float inv = amax > 0.f ? 127.f / amax : 0.f;
+  scales[gidx] = amax > 0.f ? amax / 127.f : 0.f;
+  int8_t* dst = codes + row * d + h * dh;
+  for (int t = 0; t < kMaxDh; ++t)
+    if (t < dh) dst[t] = int8_t(fminf(fmaxf(rintf(v[t] * inv), -127.f), 127.f));
+}
+
+vista_status generic_quantize(const vista_codec_desc& d, const void* y, int8_t* codes, float* scales, hipStream_t s) {
+  const int64_t groups = d.rows * d.H;
+  const int64_t blocks = (groups + 127) / 128;
+  if (blocks > 0x7FFFFFFF) return VISTA_ERR_UNSUPPORTED;
+  if (d.dtype == VISTA_BF16)
+    VISTA_LAUNCH(quantize_kernel<bf16_t>, dim3(unsigned(blocks)), dim3(128), 0, s, static_cast<const bf16_t*>(y), codes,
+                 scales, groups, d.d, d.H);
+  else
+    VISTA_LAUNCH(quantize_kernel<float>, dim3(unsigned(blocks)), dim3(128), 0, s, static_cast<const float*>(y), codes,
+                 scales, groups, d.d, d.H);
   return VISTA_OK;
 }
 

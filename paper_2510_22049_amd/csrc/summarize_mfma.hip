@@ -638,7 +638,9 @@ __global__ __launch_bounds__(256) void merge_mfma_kernel(const float* __restrict
                                                          uint16_t* __restrict__ out, int* status,
                                                          const uint16_t* __restrict__ Q, int64_t q_user_stride,
                                                          const float* __restrict__ Ks,
-                                                         const float* __restrict__ Vs, float scale) {
+                                                         const float* __restrict__ Vs, float scale,
+                                                         float* __restrict__ out_scales) {
+  __shared__ float amax_part[8][32];
   const int nqb = S / 32;
   const int qb = blockIdx.x % nqb, h = (blockIdx.x / nqb) % H, b = blockIdx.x / (nqb * H);
   // without a plan kernel in front (offsets checked on the host) the status word is cleared here
@@ -647,8 +649,15 @@ __global__ __launch_bounds__(256) void merge_mfma_kernel(const float* __restrict
   const int hf = lane >> 5, l32 = lane & 31;
   const int64_t begin = offsets[b], end = offsets[b + 1];
   uint16_t* dst = out + (int64_t(b) * S + qb * 32 + l32) * d + 32 * h + 8 * w + 4 * hf;
+  // cache codec (out_scales != null): `out` holds int8 codes, one scale per (token, head)
+  int8_t* dst8 = reinterpret_cast<int8_t*>(out) + (int64_t(b) * S + qb * 32 + l32) * d + 32 * h + 8 * w + 4 * hf;
   if (end <= begin) {
-    *reinterpret_cast<uint2*>(dst) = make_uint2(0u, 0u);
+    if (out_scales) {
+      *reinterpret_cast<uint32_t*>(dst8) = 0u;
+      if (w == 0 && hf == 0) out_scales[(int64_t(b) * S + qb * 32 + l32) * H + h] = 0.f;
+    } else {
+      *reinterpret_cast<uint2*>(dst) = make_uint2(0u, 0u);
+    }
     return;
   }
   int64_t g0 = begin / seg, g1 = (end - 1) / seg;
@@ -725,6 +734,23 @@ __global__ __launch_bounds__(256) void merge_mfma_kernel(const float* __restrict
       o3 = fmaf(vs[3], wgt, o3 * keep);
     }
     inv = 1.f / l;
+  }
+  if (out_scales) {
+    // Sec. 3.1's quantisation, fused: the head's 32 channels of a token sit in this block's
+    // eight (wave, half) groups of four; their largest magnitude goes through LDS.
+    const float y0 = o0 * inv, y1 = o1 * inv, y2 = o2 * inv, y3 = o3 * inv;
+    amax_part[2 * w + hf][l32] = fmaxf(fmaxf(fabsf(y0), fabsf(y1)), fmaxf(fabsf(y2), fabsf(y3)));
+    __syncthreads();
+    float amax = 0.f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) amax = fmaxf(amax, amax_part[k][l32]);
+    const float q = amax > 0.f ? 127.f / amax : 0.f;
+    auto code = [&](float y) __attribute__((always_inline)) {
+      return uint32_t(int(fminf(fmaxf(rintf(y * q), -127.f), 127.f))) & 0xFFu;
+    };
+    *reinterpret_cast<uint32_t*>(dst8) = code(y0) | (code(y1) << 8) | (code(y2) << 16) | (code(y3) << 24);
+    if (w == 0 && hf == 0) out_scales[(int64_t(b) * S + qb * 32 + l32) * H + h] = amax > 0.f ? amax / 127.f : 0.f;
+    return;
   }
   uint2 pk;
   pk.x = uint32_t(f32_to_bf16_bits(o0 * inv)) | (uint32_t(f32_to_bf16_bits(o1 * inv)) << 16);
@@ -826,11 +852,11 @@ vista_status mfma_summarize(const SummarizeArgs& a) {
   if (silu)
     VISTA_LAUNCH(merge_mfma_kernel<true>, dim3(unsigned(merge_blocks)), dim3(256), 0, a.stream, p.partials, a.offsets,
                  d.S, d.d, d.H, a.seg, a.G, static_cast<uint16_t*>(a.out), status, p.Q, d.q_user_stride, Ks, Vs,
-                 a.scale_plain);
+                 a.scale_plain, a.out_scales);
   else
     VISTA_LAUNCH(merge_mfma_kernel<false>, dim3(unsigned(merge_blocks)), dim3(256), 0, a.stream, p.partials, a.offsets,
                  d.S, d.d, d.H, a.seg, a.G, static_cast<uint16_t*>(a.out), status, p.Q, d.q_user_stride, Ks, Vs,
-                 a.scale_log2);
+                 a.scale_log2, a.out_scales);
   return VISTA_OK;
 }
 

@@ -127,12 +127,13 @@ size_t vista_summarize_workspace_bytes(const vista_summarize_desc* desc) {
                                          : generic_summarize_workspace(*desc, seg);
 }
 
-vista_status vista_summarize(const vista_summarize_desc* desc, const void* history_emb,
-                             const int64_t* offsets, const int64_t* offsets_host,
-                             const void* virtual_queries, const void* W_k, const void* W_v, void* out,
-                             void* workspace, size_t workspace_bytes, void* hip_stream) {
+static vista_status summarize_impl(const vista_summarize_desc* desc, const void* history_emb,
+                                   const int64_t* offsets, const int64_t* offsets_host,
+                                   const void* virtual_queries, const void* W_k, const void* W_v, void* out,
+                                   float* out_scales, void* workspace, size_t workspace_bytes, void* hip_stream) {
   vista_status st = check_summarize_desc(desc);
   if (st != VISTA_OK) return st;
+  if (out_scales && !mfma_summarize_supported(*desc)) return VISTA_ERR_UNSUPPORTED;
   if (!offsets || !virtual_queries || !W_k || !W_v || !out) return VISTA_ERR_NULL;
   if (desc->total_items > 0 && !history_emb) return VISTA_ERR_NULL;
   if (offsets_host) {
@@ -161,6 +162,7 @@ vista_status vista_summarize(const vista_summarize_desc* desc, const void* histo
   a.Wk = W_k;
   a.Wv = W_v;
   a.out = out;
+  a.out_scales = out_scales;
   a.workspace = static_cast<char*>(workspace);
   a.stream = static_cast<hipStream_t>(hip_stream);
 
@@ -176,6 +178,32 @@ vista_status vista_summarize(const vista_summarize_desc* desc, const void* histo
                   a.stream) != hipSuccess)
     return VISTA_ERR_HIP;
   return mfma_summarize_supported(*desc) ? mfma_summarize(a) : generic_summarize(a);
+}
+
+vista_status vista_summarize(const vista_summarize_desc* desc, const void* history_emb,
+                             const int64_t* offsets, const int64_t* offsets_host,
+                             const void* virtual_queries, const void* W_k, const void* W_v, void* out,
+                             void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return summarize_impl(desc, history_emb, offsets, offsets_host, virtual_queries, W_k, W_v, out, nullptr, workspace,
+                        workspace_bytes, hip_stream);
+}
+
+vista_status vista_summarize_q8(const vista_summarize_desc* desc, const void* history_emb,
+                                const int64_t* offsets, const int64_t* offsets_host,
+                                const void* virtual_queries, const void* W_k, const void* W_v, int8_t* out_codes,
+                                float* out_scales, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!out_scales) return VISTA_ERR_NULL;
+  return summarize_impl(desc, history_emb, offsets, offsets_host, virtual_queries, W_k, W_v, out_codes, out_scales,
+                        workspace, workspace_bytes, hip_stream);
+}
+
+vista_status vista_quantize_summaries(const vista_codec_desc* desc, const void* y, int8_t* codes, float* scales,
+                                      void* hip_stream) {
+  if (!desc) return VISTA_ERR_NULL;
+  if (desc->rows <= 0 || desc->d <= 0 || desc->H <= 0 || desc->d % desc->H != 0) return VISTA_ERR_SHAPE;
+  if (!dtype_ok(desc->dtype) || desc->d / desc->H > 64) return VISTA_ERR_UNSUPPORTED;
+  if (!y || !codes || !scales) return VISTA_ERR_NULL;
+  return generic_quantize(*desc, y, codes, scales, static_cast<hipStream_t>(hip_stream));
 }
 
 vista_status vista_summarize_static(const vista_summarize_desc* desc, const void* history_emb,
@@ -194,8 +222,9 @@ vista_status vista_summarize_static(const vista_summarize_desc* desc, const void
                          size_t(VISTA_STATIC_SCRATCH_BYTES), hip_stream);
 }
 
-vista_status vista_target_attend(const vista_attend_desc* desc, const void* candidates,
-                                 const void* summaries, void* out, void* hip_stream) {
+static vista_status target_attend_impl(const vista_attend_desc* desc, const void* candidates,
+                                       const void* summaries, const int8_t* codes, const float* scales, void* out,
+                                       void* hip_stream) {
   if (!desc) return VISTA_ERR_NULL;
   if (desc->B <= 0 || desc->C <= 0 || desc->S <= 0 || desc->d <= 0 || desc->H <= 0) return VISTA_ERR_SHAPE;
   if (desc->d % desc->H != 0) return VISTA_ERR_SHAPE;
@@ -203,12 +232,26 @@ vista_status vista_target_attend(const vista_attend_desc* desc, const void* cand
   if ((desc->flags & ~VISTA_FLAG_SELF_TERM) != 0) return VISTA_ERR_SHAPE;
   if (!dtype_ok(desc->dtype)) return VISTA_ERR_UNSUPPORTED;
   if (desc->S > 512 || desc->d / desc->H > 64) return VISTA_ERR_UNSUPPORTED;
-  if (!candidates || !summaries || !out) return VISTA_ERR_NULL;
+  if (!candidates || !out || (!summaries && !(codes && scales))) return VISTA_ERR_NULL;
   const float scale = desc->scale > 0.f ? desc->scale : 1.f / sqrtf(float(desc->d / desc->H));
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  if (mfma_target_attend_supported(*desc))
-    return mfma_target_attend(*desc, scale * kLog2e, candidates, summaries, out, s);
-  return generic_target_attend(*desc, scale * kLog2e, candidates, summaries, out, s);
+  // the MFMA path reads 16 codes at a time: rows of codes must then be 16-byte aligned
+  const bool aligned = !codes || (desc->d % 16 == 0 && (reinterpret_cast<uintptr_t>(codes) & 15) == 0);
+  if (mfma_target_attend_supported(*desc) && aligned)
+    return mfma_target_attend(*desc, scale * kLog2e, candidates, summaries, codes, scales, out, s);
+  return generic_target_attend(*desc, scale * kLog2e, candidates, summaries, codes, scales, out, s);
+}
+
+vista_status vista_target_attend(const vista_attend_desc* desc, const void* candidates,
+                                 const void* summaries, void* out, void* hip_stream) {
+  if (desc && !summaries) return VISTA_ERR_NULL;
+  return target_attend_impl(desc, candidates, summaries, nullptr, nullptr, out, hip_stream);
+}
+
+vista_status vista_target_attend_q8(const vista_attend_desc* desc, const void* candidates, const int8_t* codes,
+                                    const float* scales, void* out, void* hip_stream) {
+  if (desc && (!codes || !scales)) return VISTA_ERR_NULL;
+  return target_attend_impl(desc, candidates, nullptr, codes, scales, out, hip_stream);
 }
 
 vista_status vista_sglu_ffn(const vista_ffn_desc* desc, const void* y, const void* W_g, const void* W_u,

@@ -14,9 +14,18 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "vista.h")).read()
-    declared = set(re.findall(r"\b(vista_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(vista_[a-z0-9_]+)\s*\(", header))
     assert declared == set(V.EXPORTS)
     L = V.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+def test_calibration_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "vista_calibrate.h")).read()
+    declared = set(re.findall(r"\b(vista_calibrate_[a-z0-9_]+)\s*\(", header))
+    assert declared == {"vista_calibrate_issue", "vista_calibrate_lds_read", "vista_calibrate_stream_read"}
+    L = C.CDLL(os.path.join(ROOT, "paper_2510_22049_amd", "libvista_calibrate.so"))
     for name in declared:
         assert getattr(L, name) is not None
 
@@ -24,7 +33,7 @@ def test_library_exports_every_declared_symbol():
 def test_status_strings():
     L = V.lib()
     assert L.vista_status_string(0) == b"VISTA_OK"
-    for code in range(1, 7):
+    for code in range(1, 8):
         assert L.vista_status_string(code).startswith(b"VISTA_ERR_")
     assert b"unknown" in L.vista_status_string(99)
 

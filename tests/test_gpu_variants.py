@@ -154,3 +154,92 @@ def test_qla_at_the_jagged_workload_shape_and_bitwise_repeatable():
     err = assert_blocks_close(got, want, "bf16", "qla, jagged workload")
     print(f"qla, jagged workload: max block error {err:.2e}", flush=True)
     assert np.array_equal(got, run("qla", X, off, Q, Wk, Wv, c.H, "bf16", offsets_host=torch.from_numpy(off)))
+
+
+# ------------------------------------------------------------------ stage 2: self term and cache codec
+
+def attend(T, Y, H, dtype="bf16", **kw):
+    out = torch.full(T.shape, float("nan"), device="cuda", dtype=torch_dtype(dtype))
+    V.vista_target_attend(dev(T, dtype), dev(Y, dtype), out, H=H, **kw)
+    torch.cuda.synchronize()
+    return host64(out)
+
+
+@pytest.mark.parametrize("B,C,S,d,H", [(3, 130, 256, 128, 4), (2, 77, 512, 256, 8), (2, 33, 96, 128, 4), (2, 40, 288, 128, 4)])
+def test_stage2_self_term(B, C, S, d, H):
+    """Eq. 3 on the matrix cores (and S = 288 on the plain path): the candidate is one more key and value."""
+    g = np.random.default_rng(51)
+    bf = lambda x: I.round_to(np.asarray(x, dtype=np.float32), "bf16")
+    T, Y = bf(g.normal(size=(B, C, d))), bf(g.normal(size=(B, S, d)))
+    want = O.target_attend(T, Y, H, self_term=True)
+    assert_blocks_close(attend(T, Y, H, self_term=True), want, "bf16", f"stage 2 self term S={S}")
+    assert np.abs(O.target_attend(T, Y, H) - want).max() > 0.02          # the term matters
+    # long candidates: the own score c |q|^2 leaves the constant-reference range
+    T2 = bf(T * 4.0)
+    assert_blocks_close(attend(T2, Y, H, self_term=True), O.target_attend(T2, Y, H, self_term=True), "bf16",
+                        "stage 2 self term, large own scores")
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("rows,d,H", [(1000, 128, 4), (77, 256, 8), (50, 64, 1), (33, 96, 2)])
+def test_quantize_summaries_bit_exact(dtype, rows, d, H):
+    """Integer codes and fp32 scales, bit for bit (both sides take the rounding decision in fp32)."""
+    g = np.random.default_rng(52)
+    Y = I.round_to((g.normal(size=(rows, d)) * g.uniform(0.01, 30, size=(rows, 1))).astype(np.float32), dtype)
+    Y[3] = 0.0
+    Y[5, : d // H] = 0.0
+    codes = torch.full((rows, d), 99, dtype=torch.int8, device="cuda")
+    scales = torch.full((rows, H), float("nan"), device="cuda")
+    V.vista_quantize_summaries(dev(Y, dtype), codes, scales, H=H)
+    torch.cuda.synchronize()
+    wc, ws = O.quantize_summaries(Y, H)
+    assert np.array_equal(codes.cpu().numpy(), wc)
+    assert np.array_equal(scales.cpu().numpy(), ws)
+
+
+@pytest.mark.parametrize("B,C,S,d,H,self_term", [(3, 130, 256, 128, 4, False), (2, 77, 512, 256, 8, True),
+                                                 (2, 40, 288, 128, 4, False), (2, 9, 24, 64, 2, True)])
+def test_stage2_on_quantized_summaries(B, C, S, d, H, self_term):
+    g = np.random.default_rng(53)
+    bf = lambda x: I.round_to(np.asarray(x, dtype=np.float32), "bf16")
+    T, Y = bf(g.normal(size=(B, C, d))), bf(g.normal(size=(B, S, d)))
+    wc, ws = O.quantize_summaries(Y, H)
+    want = O.target_attend(T, O.dequantize_summaries(wc, ws), H, self_term=self_term)
+    out = torch.full(T.shape, float("nan"), device="cuda", dtype=torch.bfloat16)
+    V.vista_target_attend_q8(dev(T, "bf16"), torch.from_numpy(wc).cuda(), torch.from_numpy(ws).cuda(), out, H=H,
+                             self_term=self_term)
+    torch.cuda.synchronize()
+    assert_blocks_close(host64(out), want, "bf16", f"stage 2 on int8 summaries S={S}")
+
+
+@pytest.mark.parametrize("form", ["softmax", "silu"])
+@pytest.mark.parametrize("d,H,S", [(128, 4, 256), (256, 8, 512)])
+def test_stage1_with_fused_codec(form, d, H, S):
+    """The codec fused into stage 1's last kernel: dequantized codes against the unquantized oracle
+    (tolerance + half a quantisation step), and codes within one unit of the oracle's own codec
+    applied to the oracle's summaries."""
+    X, off, Q, Wk, Wv = problem(54, LENS, d, S, "bf16")
+    B = len(off) - 1
+    codes = torch.full((B, S, d), 99, dtype=torch.int8, device="cuda")
+    scales = torch.full((B, S, H), float("nan"), device="cuda")
+    offd = torch.from_numpy(off).cuda()
+    V.vista_summarize_q8(dev(X, "bf16"), offd, dev(Q, "bf16"), dev(Wk, "bf16"), dev(Wv, "bf16"), codes, scales, H=H,
+                         attn=FORMS[form], segment_items=128, offsets_host=torch.from_numpy(off))
+    torch.cuda.synchronize()
+    want = oracle(form, X, off, Q, Wk, Wv, H, False)
+    gc, gs = codes.cpu().numpy(), scales.cpu().numpy()
+    deq = O.dequantize_summaries(gc, gs)
+    step = np.repeat(gs, d // H, axis=-1).astype(np.float64)
+    for b in range(B):
+        top = np.abs(want[b]).max()
+        assert np.all(np.abs(deq[b] - want[b]) <= 2e-2 * top + 0.5 * step[b] + 1e-30), f"user {b}"
+    # codes against the oracle's codec on the oracle's summaries, where they are well conditioned:
+    # a (token, head) group whose largest magnitude is a small fraction of the user's is scaled up
+    # to +-127 all the same, and the path's own rounding noise then decides its codes
+    wc, ws_ = O.quantize_summaries(want.astype(np.float32), H)
+    tops = np.abs(want).reshape(B, -1).max(axis=1)
+    solid = np.repeat(ws_ * 127 >= 0.2 * tops[:, None, None], d // H, axis=-1)
+    assert solid.mean() > 0.5
+    assert np.abs(gc.astype(np.int32) - wc.astype(np.int32))[solid].max() <= 3
+    assert np.all(gc[1] == 0) and np.all(gs[1] == 0)                      # empty user
+    assert np.all(np.abs(gc.reshape(B, S, H, -1)).max(axis=-1)[gs > 0] == 127)
