@@ -234,6 +234,44 @@ vista_status vista_target_attend(const vista_attend_desc* desc,
                                  void* out,
                                  void* hip_stream);
 
+/* ------------------------------------------------ gradients of quasi-linear attention */
+
+/*
+ * Backward of VISTA_ATTN_QLA (App. B.1: Eqs. 7, 9, 11 give dQ = dO Z, dK = V W^T, dV = K W for
+ * the linear core, with the d_h x d_h intermediates Z = V^T K and W = Q^T dO; with the
+ * activations of Sec. 3.2.2 in place every product is taken on the activated operand and
+ * multiplied by the activation's derivative, as the appendix shows for its shifted-ELU
+ * variant).  Per user and head, with A = SiLU(Q), P = SiLU(K), Zs = P^T V, G = SiLU(Zs):
+ *     dQ  = (dO G^T) * SiLU'(Q)
+ *     dZs = (A^T dO) * SiLU'(Zs)
+ *     dV  = P dZs,      dK = (V dZs^T) * SiLU'(K)
+ * K = X W_k and V = X W_v are recomputed from the history as in the forward call; the
+ * gradients are with respect to these projected keys and values (their own backward --
+ * dX = dK W_k^T + dV W_v^T, dW = X^T dK -- is a pair of plain matrix products outside this path).
+ *
+ *   desc            as for the forward call: attn = VISTA_ATTN_QLA, flags = 0, scale = 0
+ *   d_out           device [B, S, d]  dtype   gradient of the loss w.r.t. the forward output
+ *   d_queries       device [B, S, d]  dtype   per user, also when the queries are shared
+ *                                             (the gradient of shared seeds is the sum over users)
+ *   d_keys, d_values device [N, d]    dtype   rows of users without history do not exist; every row is written
+ *   workspace       >= vista_qla_backward_workspace_bytes(desc), 256-byte aligned
+ * Supported: the shapes vista_summarize takes with VISTA_ATTN_QLA.
+ */
+size_t vista_qla_backward_workspace_bytes(const vista_summarize_desc* desc);
+vista_status vista_qla_backward(const vista_summarize_desc* desc,
+                                const void* history_emb,
+                                const int64_t* offsets,
+                                const int64_t* offsets_host,
+                                const void* virtual_queries,
+                                const void* W_k,
+                                const void* W_v,
+                                const void* d_out,
+                                void* d_queries,
+                                void* d_keys,
+                                void* d_values,
+                                void* workspace, size_t workspace_bytes,
+                                void* hip_stream);
+
 /* ------------------------------------------------ cache codec (int8) */
 
 /*

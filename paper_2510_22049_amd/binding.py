@@ -36,6 +36,8 @@ EXPORTS = (
     "vista_target_attend_q8",
     "vista_quantize_summaries",
     "vista_summarize_q8",
+    "vista_qla_backward_workspace_bytes",
+    "vista_qla_backward",
     "vista_sglu_ffn",
 )
 
@@ -95,6 +97,10 @@ def lib() -> C.CDLL:
     L.vista_summarize_static.argtypes = [C.POINTER(SummarizeDesc), vp, vp, vp, vp, vp, vp, vp, vp]
     L.vista_summarize_q8.restype = C.c_int
     L.vista_summarize_q8.argtypes = [C.POINTER(SummarizeDesc), vp, vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+    L.vista_qla_backward_workspace_bytes.restype = C.c_size_t
+    L.vista_qla_backward_workspace_bytes.argtypes = [C.POINTER(SummarizeDesc)]
+    L.vista_qla_backward.restype = C.c_int
+    L.vista_qla_backward.argtypes = [C.POINTER(SummarizeDesc)] + [vp] * 11 + [C.c_size_t, vp]
     L.vista_quantize_summaries.restype = C.c_int
     L.vista_quantize_summaries.argtypes = [C.POINTER(CodecDesc), vp, vp, vp, vp]
     L.vista_target_attend_q8.restype = C.c_int
@@ -208,6 +214,29 @@ def vista_summarize_q8(history_emb, offsets, virtual_queries, W_k, W_v, out_code
                                   _dev(W_k, "W_k"), _dev(W_v, "W_v"), _dev(out_codes, "out_codes"),
                                   _dev(out_scales, "out_scales"), _dev(workspace, "workspace"), workspace.numel(),
                                   _stream())
+    if st != VISTA_OK:
+        raise VistaError(st)
+    return workspace
+
+
+def vista_qla_backward(history_emb, offsets, virtual_queries, W_k, W_v, d_out, d_queries, d_keys, d_values, *, H,
+                       segment_items=0, offsets_host=None, workspace=None):
+    """Gradients of quasi-linear attention: d_out [B,S,d] -> d_queries [B,S,d], d_keys / d_values [N,d]."""
+    B = offsets.numel() - 1
+    S, d = virtual_queries.shape[-2:]
+    N = history_emb.shape[0]
+    desc = summarize_desc(B, S, d, H, _dtype_code(history_emb), N, virtual_queries.dim() == 3, 0.0,
+                          segment_items, VISTA_ATTN_QLA)
+    need = lib().vista_qla_backward_workspace_bytes(C.byref(desc))
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=history_emb.device)
+    host = offsets_host.contiguous().data_ptr() if offsets_host is not None else None
+    st = lib().vista_qla_backward(C.byref(desc), _dev(history_emb, "history_emb") if N else None,
+                                  _dev(offsets, "offsets"), host, _dev(virtual_queries, "virtual_queries"),
+                                  _dev(W_k, "W_k"), _dev(W_v, "W_v"), _dev(d_out, "d_out"),
+                                  _dev(d_queries, "d_queries"), _dev(d_keys, "d_keys") if N else None,
+                                  _dev(d_values, "d_values") if N else None, _dev(workspace, "workspace"),
+                                  workspace.numel(), _stream())
     if st != VISTA_OK:
         raise VistaError(st)
     return workspace

@@ -342,6 +342,136 @@ __global__ __launch_bounds__(256) void qla_finish_kernel(const float* __restrict
   }
 }
 
+// ---------------------------------------------- quasi-linear attention: gradients (App. B.1)
+__device__ __forceinline__ float silu_f(float x) { return x / (1.f + expf(-x)); }
+__device__ __forceinline__ float silu_prime_f(float x) {
+  const float sg = 1.f / (1.f + expf(-x));
+  return sg * (1.f + x * (1.f - sg));
+}
+
+// Per (user, head): the state Zs (ascending-order sum of the user's records), G = SiLU(Zs),
+//   dQ = (dO G^T) * SiLU'(Q)         written to d_queries,
+//   dZs = (SiLU(Q)^T dO) * SiLU'(Zs) written to dz [B][H][dh][dh] fp32 for the item pass.
+// grid (B, H), 256 threads; queries pass through LDS in runs of 64.
+template <typename T>
+__global__ __launch_bounds__(256) void qla_bwd_state_kernel(const float* __restrict__ partials,
+                                                            const int64_t* __restrict__ offsets, int S, int d, int H,
+                                                            int seg, int64_t G, const T* __restrict__ Q,
+                                                            int64_t q_user_stride, const T* __restrict__ dO,
+                                                            T* __restrict__ dQ, float* __restrict__ dz) {
+  __shared__ float zs[kMaxDh * kMaxDh];        // Zs, then SiLU'(Zs)
+  __shared__ float gt[kMaxDh * (kMaxDh + 1)];  // G transposed: gt[c][a]
+  __shared__ float qa[64][kMaxDh + 1];         // SiLU(q) of the run
+  __shared__ float dy[64][kMaxDh + 1];         // dO of the run
+  const int dh = d / H;
+  const int b = blockIdx.x, h = blockIdx.y;
+  const int64_t begin = offsets[b], end = offsets[b + 1];
+  const int zz = dh * dh;
+  float* dzb = dz + (int64_t(b) * H + h) * zz;
+  T* dq = dQ + int64_t(b) * S * d + h * dh;
+  if (end <= begin) {       // no history: the forward output is zero whatever Q is
+    for (int e = threadIdx.x; e < S * dh; e += blockDim.x) store_as(dq + int64_t(e / dh) * d + (e % dh), 0.f);
+    for (int e = threadIdx.x; e < zz; e += blockDim.x) dzb[e] = 0.f;
+    return;
+  }
+  int64_t g0 = begin / seg, g1 = (end - 1) / seg;
+  if (g0 < 0) g0 = 0;
+  if (g1 > G - 1) g1 = G - 1;
+  for (int e = threadIdx.x; e < zz; e += blockDim.x) {
+    float acc = 0.f;
+    for (int64_t g = g0; g <= g1; g += 8) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = g + u <= g1 ? partials[((g + u + b) * H + h) * zz + e] : 0.f;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) acc += v[u];
+    }
+    zs[e] = silu_prime_f(acc);
+    gt[(e % dh) * (dh + 1) + e / dh] = silu_f(acc);
+  }
+  // this thread's entries of dG = SiLU(Q)^T dO: e = threadIdx.x + 256 k
+  float dg[kMaxDh * kMaxDh / 256];
+#pragma unroll
+  for (int k = 0; k < kMaxDh * kMaxDh / 256; ++k) dg[k] = 0.f;
+  for (int i0 = 0; i0 < S; i0 += 64) {
+    __syncthreads();
+    for (int e = threadIdx.x; e < 64 * dh; e += blockDim.x) {
+      const int r = e / dh, a = e % dh;
+      const bool on = i0 + r < S;
+      const float q = on ? to_f32(Q[q_user_stride * b + int64_t(i0 + r) * d + h * dh + a]) : 0.f;
+      qa[r][a] = silu_f(q);
+      dy[r][a] = on ? to_f32(dO[(int64_t(b) * S + i0 + r) * d + h * dh + a]) : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < kMaxDh * kMaxDh / 256; ++k) {
+      const int e = threadIdx.x + 256 * k;
+      if (e < zz) {
+        const int a = e / dh, c = e % dh;
+        float acc = dg[k];
+        for (int r = 0; r < 64; ++r) acc = fmaf(qa[r][a], dy[r][c], acc);
+        dg[k] = acc;
+      }
+    }
+    // dQ of the run: one (query, channel) pair per thread and step
+    for (int e = threadIdx.x; e < 64 * dh; e += blockDim.x) {
+      const int r = e / dh, a = e % dh;
+      if (i0 + r < S) {
+        float acc = 0.f;
+        for (int c = 0; c < dh; ++c) acc = fmaf(dy[r][c], gt[c * (dh + 1) + a], acc);
+        const float q = to_f32(Q[q_user_stride * b + int64_t(i0 + r) * d + h * dh + a]);
+        store_as(dq + int64_t(i0 + r) * d + a, acc * silu_prime_f(q));
+      }
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < kMaxDh * kMaxDh / 256; ++k) {
+    const int e = threadIdx.x + 256 * k;
+    if (e < zz) dzb[e] = dg[k] * zs[e];
+  }
+}
+
+// Per item and head (plain path): dV = SiLU(k) dZs, dK = (v dZs^T) * SiLU'(k), from fp32 K, V.
+// One thread per (item, head).
+template <typename T>
+__global__ void qla_bwd_items_kernel(const float* __restrict__ K, const float* __restrict__ V,
+                                     const int64_t* __restrict__ offsets, int B, int d, int H, int64_t N,
+                                     const float* __restrict__ dz, T* __restrict__ dK, T* __restrict__ dV) {
+  const int64_t idx = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (idx >= N * H) return;
+  const int64_t j = idx / H;
+  const int h = int(idx - j * H);
+  const int dh = d / H;
+  int b = 0;                 // the last user starting at or before row j (empty users own no rows);
+  {                          // searched per thread: rows of one wave belong to different users
+    int hi = B;
+    while (hi - b > 1) {
+      const int mid = (b + hi) >> 1;
+      if (offsets[mid] <= j) b = mid; else hi = mid;
+    }
+  }
+  const float* z = dz + (int64_t(b) * H + h) * dh * dh;
+  const float* k = K + j * d + h * dh;
+  const float* v = V + j * d + h * dh;
+  float p[kMaxDh], vv[kMaxDh];
+  for (int a = 0; a < kMaxDh; ++a) {
+    p[a] = a < dh ? silu_f(k[a]) : 0.f;
+    vv[a] = a < dh ? v[a] : 0.f;
+  }
+  for (int c = 0; c < dh; ++c) {
+    float acc = 0.f;
+    for (int a = 0; a < kMaxDh; ++a)
+      if (a < dh) acc = fmaf(p[a], z[a * dh + c], acc);
+    store_as(dV + j * d + h * dh + c, acc);
+  }
+  for (int a = 0; a < dh; ++a) {
+    float acc = 0.f;
+    for (int c = 0; c < kMaxDh; ++c)
+      if (c < dh) acc = fmaf(vv[c], z[a * dh + c], acc);
+    store_as(dK + j * d + h * dh + a, acc * silu_prime_f(k[a]));
+  }
+}
+
 static size_t generic_partials_bytes(const vista_summarize_desc& d, int seg) {
   int64_t G = (d.total_items + seg - 1) / seg;
   int dh = d.d / d.H;
@@ -424,6 +554,58 @@ static vista_status generic_summarize_t(const SummarizeArgs& a) {
 vista_status generic_summarize(const SummarizeArgs& a) {
   if (a.desc.d / a.desc.H > kMaxDh) return VISTA_ERR_UNSUPPORTED;
   return a.desc.dtype == VISTA_BF16 ? generic_summarize_t<bf16_t>(a) : generic_summarize_t<float>(a);
+}
+
+// Workspace of the backward call: the forward layout (header, plan, state records, fp32 K and V
+// on the plain path) followed by dZs [B][H][dh][dh] fp32.
+size_t qla_backward_workspace(const vista_summarize_desc& d, int seg) {
+  const int dh = d.d / d.H;
+  return generic_summarize_workspace(d, seg) + align256(size_t(d.B) * d.H * dh * dh * sizeof(float));
+}
+
+template <typename T>
+static vista_status qla_backward_t(const SummarizeArgs& a, const void* d_out, void* d_queries, void* d_keys,
+                                   void* d_values) {
+  const vista_summarize_desc& d = a.desc;
+  const int64_t N = d.total_items;
+  const int dh = d.d / d.H;
+  char* base = a.workspace + kHeaderBytes + plan_bytes(a.G);
+  float* partials = reinterpret_cast<float*>(base);
+  const size_t kv_each = mfma_qla_supported(d) ? 0 : align256(size_t(N) * d.d * sizeof(float));
+  float* K = reinterpret_cast<float*>(base + align256(generic_partials_bytes(d, a.seg)));
+  float* V = K + kv_each / sizeof(float);
+  float* dz = reinterpret_cast<float*>(a.workspace + generic_summarize_workspace(d, a.seg));
+  const bool mfma = mfma_qla_supported(d);
+  if (N > 0) {
+    if (mfma) {
+      const vista_status st = mfma_qla_state(a, partials);
+      if (st != VISTA_OK) return st;
+    } else {
+      const int64_t blocks = (N * d.d + 255) / 256;
+      if (blocks > 0x7FFFFFFF) return VISTA_ERR_UNSUPPORTED;
+      VISTA_LAUNCH(project_kernel<T>, dim3(unsigned(blocks)), dim3(256), 0, a.stream, static_cast<const T*>(a.X),
+                   static_cast<const T*>(a.Wk), static_cast<const T*>(a.Wv), K, V, N, d.d);
+      VISTA_LAUNCH(qla_state_kernel, dim3(unsigned(a.G), d.H), dim3(256), 0, a.stream, K, V, a.offsets, d.B, d.d, d.H,
+                   N, a.seg, a.seg_user, partials);
+    }
+  }
+  VISTA_LAUNCH(qla_bwd_state_kernel<T>, dim3(d.B, d.H), dim3(256), 0, a.stream, partials, a.offsets, d.S, d.d, d.H,
+               a.seg, a.G, static_cast<const T*>(a.Q), d.q_user_stride, static_cast<const T*>(d_out),
+               static_cast<T*>(d_queries), dz);
+  if (N > 0) {
+    if (mfma) return mfma_qla_backward_items(a, dz, d_keys, d_values);
+    const int64_t blocks = (N * d.H + 127) / 128;
+    if (blocks > 0x7FFFFFFF) return VISTA_ERR_UNSUPPORTED;
+    VISTA_LAUNCH(qla_bwd_items_kernel<T>, dim3(unsigned(blocks)), dim3(128), 0, a.stream, K, V, a.offsets, d.B, d.d,
+                 d.H, N, dz, static_cast<T*>(d_keys), static_cast<T*>(d_values));
+  }
+  (void)dh;
+  return VISTA_OK;
+}
+
+vista_status qla_backward(const SummarizeArgs& a, const void* d_out, void* d_queries, void* d_keys, void* d_values) {
+  return a.desc.dtype == VISTA_BF16 ? qla_backward_t<bf16_t>(a, d_out, d_queries, d_keys, d_values)
+                                    : qla_backward_t<float>(a, d_out, d_queries, d_keys, d_values);
 }
 
 // ------------------------------------------------------------------ stage 2

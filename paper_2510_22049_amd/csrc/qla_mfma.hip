@@ -220,6 +220,193 @@ __global__ __launch_bounds__(D * 2, 2) void qla_state_mfma_kernel(QlaParams p) {
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// Backward, item pass (App. B.1): for every item of a user and every head
+//     dV = SiLU(k) dZs,      dK = (v dZs^T) * SiLU'(k),
+// with dZs (d_h x d_h, per user and head) already formed.  Same streaming structure as the
+// forward state kernel; here the projections are formed transposed, K^T = W_k,h^T X^T and
+// V^T = W_v,h^T X^T (items on the lane index), so that SiLU(K)^T and V^T are B operands as they
+// leave the accumulators and both products come out transposed again, one item per lane:
+//     dV^T = dZs^T SiLU(K)^T,      dP^T = dZs V^T,      dK^T = dP^T * SiLU'(K)^T.
+// The two A operands hold dZs with its contraction index in the accumulators' register order;
+// they are reloaded when the stream passes from one user to the next.
+template <int D>
+__global__ __launch_bounds__(D * 2, 2) void qla_bwd_items_mfma_kernel(QlaParams p, const float* __restrict__ dz,
+                                                                      uint16_t* __restrict__ dK,
+                                                                      uint16_t* __restrict__ dV) {
+  constexpr int NW = D / 32;
+  constexpr int NT = NW * 64;
+  constexpr int CH = D / 8;
+  constexpr int KS = D / 16;
+  constexpr int CPT = kTile * CH / NT;
+  __shared__ uint4 xbuf[kRing][CH * 32];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int hf = lane >> 5, l32 = lane & 31;
+  const int h = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+  bf16x8 wk[KS], wv[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    Pack8 a, b;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int64_t at = int64_t(16 * ks + 8 * hf + j) * D + 32 * h + l32;
+      a.h[j] = f32_to_bf16_bits(__uint_as_float(uint32_t(p.Wk[at]) << 16) * -kLog2e);   // t = -k log2(e)
+      b.h[j] = p.Wv[at];
+    }
+    wk[ks] = a.v;
+    wv[ks] = b.v;
+    __builtin_amdgcn_sched_barrier(0);
+  }
+
+  const int wave = h;
+  auto fetch = [&](const TileCursor& c, int xb) __attribute__((always_inline)) {
+    const int last = c.rows() - 1;
+    const char* base = reinterpret_cast<const char*>(p.X) + c.row * (D * 2);
+#pragma unroll
+    for (int k = 0; k < CPT; ++k) {
+      const int slot = k * NT + tid;
+      int rel = slot & 31;
+      if (rel > last) rel = last;
+      const uint32_t voff = uint32_t(rel) * (D * 2) + uint32_t(slot >> 5) * 16;
+      const uint32_t lds_base = uint32_t(reinterpret_cast<uintptr_t>(
+          (void __attribute__((address_space(3)))*)(&xbuf[xb][k * NT + wave * 64])));
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                   :
+                   : "s"(lds_base), "v"(voff), "s"(base)
+                   : "memory", "m0");
+    }
+  };
+  auto wait_vm = [&](auto n_c) __attribute__((always_inline)) {
+    constexpr int n = decltype(n_c)::value;
+    __builtin_amdgcn_s_waitcnt((n & 0xF) | ((n >> 4) << 14) | 0x0F70);
+  };
+
+  // A operands of the two products for the current user: element j of part q pairs with
+  // accumulator register 8 q + j, i.e. with contraction index acc_row0(8 q + j) + 4 hf.
+  bf16x8 zt[2], zn[2];      // zt: dZs^T (rows c, contraction a);  zn: dZs (rows a, contraction c)
+  auto load_dz = [&](int user) __attribute__((always_inline)) {
+    const float* z = dz + (int64_t(user) * p.H + h) * 1024;
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      Pack8 t, n;
+#pragma unroll
+      for (int j = 0; j < 8; j += 2) {
+        const int r0 = acc_row0(8 * q + j) + 4 * hf, r1 = acc_row0(8 * q + j + 1) + 4 * hf;
+        t.w[j / 2] = cvt_pk_bf16(z[r0 * 32 + l32], z[r1 * 32 + l32]);     // dZs^T[c = l32][a = r]
+        n.w[j / 2] = cvt_pk_bf16(z[l32 * 32 + r0], z[l32 * 32 + r1]);     // dZs[a = l32][c = r]
+      }
+      zt[q] = t.v;
+      zn[q] = n.v;
+    }
+  };
+
+  for (int64_t g = blockIdx.x; g * p.seg < p.N; g += gridDim.x) {
+    const int64_t seg_begin = g * p.seg;
+    const int64_t seg_end = (seg_begin + p.seg < p.N) ? seg_begin + p.seg : p.N;
+    TileCursor ca, cf;
+    ca.init(p.offsets, p.B, p.seg_user ? __builtin_amdgcn_readfirstlane(p.seg_user[g]) : find_user(p.offsets, p.B, seg_begin),
+            seg_begin, seg_end);
+    if (!ca.valid) continue;
+    cf = ca;
+    load_dz(ca.user);
+
+    fetch(cf, 0);
+    cf.advance(p.offsets, p.B, seg_end);
+    fetch(cf, 1);
+    cf.advance(p.offsets, p.B, seg_end);
+    fetch(cf, 2);
+    cf.advance(p.offsets, p.B, seg_end);
+    wait_vm(Int<2 * CPT>{});
+    lds_barrier();
+
+    int xb = 0;
+    for (;;) {
+      const int nvalid = ca.rows();
+      Pack8 pk0, pk1, pv0, pv1;       // SiLU(K)^T and V^T as B operands (two halves of the 16 registers)
+      float dsilu[16];                // SiLU'(k) of this lane's item, channels in register order
+      {
+        f32x16 ak = {0};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          Pack8 x;
+          x.u = xbuf[xb][(2 * ks + hf) * 32 + l32];
+          ak = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wk[ks], x.v, ak, 0, 0, 0);
+          if (ks % 4 == 3) __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int i = 0; i < 16; i += 2) {
+          float f[2];
+#pragma unroll
+          for (int u = 0; u < 2; ++u) {
+            const float t = ak[i + u];                                  // -k log2(e)
+            const float sg = __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(t));
+            const float k = t * -0.69314718056f;
+            f[u] = k * sg;
+            dsilu[i + u] = sg * fmaf(k, 1.f - sg, 1.f);
+          }
+          const uint32_t w = cvt_pk_bf16(f[0], f[1]);
+          if (i < 8) pk0.w[i / 2] = w; else pk1.w[(i - 8) / 2] = w;
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      {
+        f32x16 av = {0};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          Pack8 x;
+          x.u = xbuf[xb][(2 * ks + hf) * 32 + l32];
+          av = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv[ks], x.v, av, 0, 0, 0);
+          if (ks % 4 == 3) __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int i = 0; i < 16; i += 2) {
+          const uint32_t w = cvt_pk_bf16(av[i], av[i + 1]);
+          if (i < 8) pv0.w[i / 2] = w; else pv1.w[(i - 8) / 2] = w;
+        }
+      }
+      // Both projections have read the tile's rows.  Everything this wave has in flight -- the
+      // stores of the previous tile, issued a projection ago, and the requests for the next two
+      // tiles -- must be done before the barrier (loads and stores complete out of order with
+      // each other, so the count alone cannot tell them apart); then the slot is refilled.
+      wait_vm(Int<0>{});
+      lds_barrier();
+      fetch(cf, xb);
+      cf.advance(p.offsets, p.B, seg_end);
+
+      f32x16 gv = {0}, gp = {0};
+      gv = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zt[0], pk0.v, gv, 0, 0, 0);      // dV^T = dZs^T SiLU(K)^T
+      gv = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zt[1], pk1.v, gv, 0, 0, 0);
+      gp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zn[0], pv0.v, gp, 0, 0, 0);      // dP^T = dZs V^T
+      gp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zn[1], pv1.v, gp, 0, 0, 0);
+      // lane = item l32 of the tile; register group of four = channels acc_row0(4 q) + 4 hf + 0..3
+      if (l32 < nvalid) {
+        const int64_t row = ca.row + l32;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int64_t at = row * D + 32 * h + acc_row0(4 * q) + 4 * hf;
+          uint2 ov, ok;
+          ov.x = cvt_pk_bf16(gv[4 * q], gv[4 * q + 1]);
+          ov.y = cvt_pk_bf16(gv[4 * q + 2], gv[4 * q + 3]);
+          ok.x = cvt_pk_bf16(gp[4 * q] * dsilu[4 * q], gp[4 * q + 1] * dsilu[4 * q + 1]);
+          ok.y = cvt_pk_bf16(gp[4 * q + 2] * dsilu[4 * q + 2], gp[4 * q + 3] * dsilu[4 * q + 3]);
+          *reinterpret_cast<uint2*>(dV + at) = ov;
+          *reinterpret_cast<uint2*>(dK + at) = ok;
+        }
+      }
+      const int prev_user = ca.user;
+      ca.advance(p.offsets, p.B, seg_end);
+      xb = xb == kRing - 1 ? 0 : xb + 1;
+      if (!ca.valid) break;
+      if (ca.user != prev_user) load_dz(ca.user);
+    }
+    wait_vm(Int<0>{});
+    lds_barrier();
+  }
+}
+
 }  // namespace
 
 bool mfma_qla_supported(const vista_summarize_desc& d) {
@@ -247,6 +434,30 @@ vista_status mfma_qla_state(const SummarizeArgs& a, float* partials) {
     VISTA_LAUNCH(qla_state_mfma_kernel<128>, dim3(blocks), dim3(256), 0, a.stream, p);
   else
     VISTA_LAUNCH(qla_state_mfma_kernel<256>, dim3(blocks), dim3(512), 0, a.stream, p);
+  return VISTA_OK;
+}
+
+vista_status mfma_qla_backward_items(const SummarizeArgs& a, const float* dz, void* d_keys, void* d_values) {
+  const vista_summarize_desc& d = a.desc;
+  QlaParams p;
+  p.X = static_cast<const uint16_t*>(a.X);
+  p.offsets = a.offsets;
+  p.seg_user = a.seg_user;
+  p.Wk = static_cast<const uint16_t*>(a.Wk);
+  p.Wv = static_cast<const uint16_t*>(a.Wv);
+  p.partials = nullptr;
+  p.B = d.B;
+  p.H = d.H;
+  p.N = d.total_items;
+  p.seg = a.seg;
+  const int64_t resident = d.d == 128 ? 512 : 256;
+  const unsigned blocks = unsigned(a.G < resident ? a.G : resident);
+  if (d.d == 128)
+    VISTA_LAUNCH(qla_bwd_items_mfma_kernel<128>, dim3(blocks), dim3(256), 0, a.stream, p, dz,
+                 static_cast<uint16_t*>(d_keys), static_cast<uint16_t*>(d_values));
+  else
+    VISTA_LAUNCH(qla_bwd_items_mfma_kernel<256>, dim3(blocks), dim3(512), 0, a.stream, p, dz,
+                 static_cast<uint16_t*>(d_keys), static_cast<uint16_t*>(d_values));
   return VISTA_OK;
 }
 

@@ -206,6 +206,52 @@ vista_status vista_quantize_summaries(const vista_codec_desc* desc, const void* 
   return generic_quantize(*desc, y, codes, scales, static_cast<hipStream_t>(hip_stream));
 }
 
+size_t vista_qla_backward_workspace_bytes(const vista_summarize_desc* desc) {
+  if (check_summarize_desc(desc) != VISTA_OK || desc->attn != VISTA_ATTN_QLA || desc->flags != 0) return 0;
+  return qla_backward_workspace(*desc, resolve_segment(desc));
+}
+
+vista_status vista_qla_backward(const vista_summarize_desc* desc, const void* history_emb, const int64_t* offsets,
+                                const int64_t* offsets_host, const void* virtual_queries, const void* W_k,
+                                const void* W_v, const void* d_out, void* d_queries, void* d_keys, void* d_values,
+                                void* workspace, size_t workspace_bytes, void* hip_stream) {
+  vista_status st = check_summarize_desc(desc);
+  if (st != VISTA_OK) return st;
+  if (desc->attn != VISTA_ATTN_QLA || desc->flags != 0) return VISTA_ERR_UNSUPPORTED;
+  if (!offsets || !virtual_queries || !W_k || !W_v || !d_out || !d_queries) return VISTA_ERR_NULL;
+  if (desc->total_items > 0 && (!history_emb || !d_keys || !d_values)) return VISTA_ERR_NULL;
+  if (offsets_host) {
+    if (offsets_host[0] != 0 || offsets_host[desc->B] != desc->total_items) return VISTA_ERR_OFFSETS;
+    for (int b = 0; b < desc->B; ++b)
+      if (offsets_host[b + 1] < offsets_host[b]) return VISTA_ERR_OFFSETS;
+  }
+  const size_t need = vista_qla_backward_workspace_bytes(desc);
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0 || workspace_bytes < need)
+    return VISTA_ERR_WORKSPACE;
+  SummarizeArgs a;
+  a.desc = *desc;
+  a.seg = resolve_segment(desc);
+  a.G = (desc->total_items + a.seg - 1) / a.seg;
+  if (a.G + desc->B > 0x7FFFFFFF) return VISTA_ERR_UNSUPPORTED;
+  a.scale_log2 = kLog2e;
+  a.scale_plain = 1.f;
+  a.X = history_emb;
+  a.offsets = offsets;
+  a.Q = virtual_queries;
+  a.Wk = W_k;
+  a.Wv = W_v;
+  a.out = nullptr;
+  a.out_scales = nullptr;
+  a.workspace = static_cast<char*>(workspace);
+  a.stream = static_cast<hipStream_t>(hip_stream);
+  int* seg_user = reinterpret_cast<int*>(a.workspace + kHeaderBytes);
+  a.seg_user = seg_user;
+  if (launch_plan(offsets, desc->B, desc->total_items, a.seg, a.G, reinterpret_cast<int*>(workspace), seg_user,
+                  a.stream) != hipSuccess)
+    return VISTA_ERR_HIP;
+  return qla_backward(a, d_out, d_queries, d_keys, d_values);
+}
+
 vista_status vista_summarize_static(const vista_summarize_desc* desc, const void* history_emb,
                                     const int64_t* offsets, const int64_t* offsets_host,
                                     const void* virtual_queries, const void* W_k, const void* W_v, void* out,

@@ -7,7 +7,7 @@ import torch
 from oracle import vista_oracle as O
 from paper_2510_22049_amd import binding as V
 from paper_2510_22049_amd import inputs as I
-from tests.helpers import assert_blocks_close, dev, host64, torch_dtype
+from tests.helpers import TOL, assert_blocks_close, block_errors, dev, host64, torch_dtype
 
 pytestmark = pytest.mark.gpu
 
@@ -243,3 +243,58 @@ def test_stage1_with_fused_codec(form, d, H, S):
     assert np.abs(gc.astype(np.int32) - wc.astype(np.int32))[solid].max() <= 3
     assert np.all(gc[1] == 0) and np.all(gs[1] == 0)                      # empty user
     assert np.all(np.abs(gc.reshape(B, S, H, -1)).max(axis=-1)[gs > 0] == 127)
+
+
+# ------------------------------------------------------------------ gradients of quasi-linear attention
+
+def qla_backward_oracle(X, off, Q, Wk, Wv, dO, H):
+    B = len(off) - 1
+    dQ = np.zeros((B,) + Q.shape[-2:])
+    dK, dV = np.zeros(X.shape), np.zeros(X.shape)
+    X64 = X.astype(np.float64)
+    for b in range(B):
+        if off[b + 1] == off[b]:
+            continue
+        Xb = X64[off[b]:off[b + 1]]
+        q = Q[b] if Q.ndim == 3 else Q
+        dQ[b], dK[off[b]:off[b + 1]], dV[off[b]:off[b + 1]] = O.qla_backward(q, Xb @ Wk.astype(np.float64),
+                                                                            Xb @ Wv.astype(np.float64), dO[b], H)
+    return dQ, dK, dV
+
+
+@pytest.mark.parametrize("dtype,d,H,S,per_user", [("f32", 64, 2, 24, False), ("bf16", 64, 4, 40, True),
+                                                  ("bf16", 128, 4, 256, False), ("bf16", 128, 4, 40, True),
+                                                  ("bf16", 256, 8, 128, False)])
+@pytest.mark.parametrize("seg", [0, 96])
+def test_qla_backward(dtype, d, H, S, per_user, seg):
+    """dQ per user, dK and dV per item against the oracle's gradients (App. B.1); jagged users incl.
+    empty, one item, ragged tiles; plain path and matrix-core path."""
+    lens = [700, 0, 1, 31, 32, 33, 1100, 64, 0, 95]
+    X, off, Q, Wk, Wv = problem(61, lens, d, S, dtype, per_user)
+    g = np.random.default_rng(62)
+    B = len(lens)
+    dO = I.round_to(g.normal(size=(B, S, d)).astype(np.float32), dtype)
+    tdt = torch_dtype(dtype)
+    dQ = torch.full((B, S, d), float("nan"), device="cuda", dtype=tdt)
+    dK = torch.full(X.shape, float("nan"), device="cuda", dtype=tdt)
+    dV = torch.full(X.shape, float("nan"), device="cuda", dtype=tdt)
+    V.vista_qla_backward(dev(X, dtype), torch.from_numpy(off).cuda(), dev(Q, dtype), dev(Wk, dtype), dev(Wv, dtype),
+                         dev(dO, dtype), dQ, dK, dV, H=H, segment_items=seg, offsets_host=torch.from_numpy(off))
+    torch.cuda.synchronize()
+    wQ, wK, wV = qla_backward_oracle(X, off, Q, Wk, Wv, dO, H)
+    assert_blocks_close(host64(dQ), wQ, dtype, "qla backward dQ")
+    assert np.all(host64(dQ)[1] == 0) and np.all(host64(dQ)[8] == 0)
+    gK, gV = host64(dK), host64(dV)
+    assert np.all(np.isfinite(gK)) and np.all(np.isfinite(gV))
+    # Tolerance of the per-item gradients with bf16 operands: they carry SiLU'(Zs), and the state
+    # Zs -- a sum over the L items of bf16-rounded products -- is known to about 2^-8 of its typical
+    # magnitude sqrt(L) |SiLU(k) v|; where an entry of Zs is near zero, SiLU' moves by up to half
+    # that absolute error (|SiLU''| <= 1/2), i.e. by ~2^-9 sqrt(L) |SiLU(k) v| ~ 2 % at L ~ 1000.
+    # Hence 5e-2 per user block for bf16 (fp32 keeps 1e-4).
+    tol = 5e-2 if dtype == "bf16" else TOL[dtype]
+    for b in range(B):                      # per-user blocks of the per-item gradients
+        if off[b + 1] > off[b]:
+            sl = slice(off[b], off[b + 1])
+            for name, got_, want_ in (("dK", gK[sl], wK[sl]), ("dV", gV[sl], wV[sl])):
+                err = block_errors(got_[None], want_[None])[0]
+                assert err <= tol, f"qla backward {name} user {b}: {err:.3e} > {tol:.0e}"
