@@ -14,7 +14,9 @@ their own, the other legs (each timed over its own K steps, K scaled down for th
   lifelong   stage 1 on 8 users x 1,000,000 items (split-L merge);
   end_to_end 256 users, lengths U[10k,100k], two stacked layers (d=256, 8 heads, S=512) with
              the gated block between, then 256 candidates per user: per call and end to end;
-  silu, qla  stage 1 with the SiLU score form / quasi-linear attention on the jagged batch.
+  silu, qla  stage 1 with the SiLU score form / quasi-linear attention on the jagged batch;
+  qla_backward  gradients of quasi-linear attention on the jagged batch (dQ, dK, dV);
+  stage2_q8  stage 2 on int8-quantized summaries (the cache codec), serving workload.
 `calibration` holds what this machine sustains, measured in the same run with the instructions
 the kernels are made of (matrix-pipe rate and the shader clock it implies, HBM read
 bandwidth, issue cost of v_exp_f32 / v_cvt_pk / v_add / MFMA, LDS operand reads, and the
@@ -260,7 +262,7 @@ def main() -> None:
     ap.add_argument("--segment-items", type=int, default=0)
     ap.add_argument("--calibrate", action="store_true", help="print the full calibration table to stderr")
     ap.add_argument("--no-calibration", action="store_true", help="skip the calibration kernels")
-    ap.add_argument("--legs", default="stage1,stage2,lifelong,end_to_end,silu,qla",
+    ap.add_argument("--legs", default="stage1,stage2,stage2_q8,lifelong,end_to_end,silu,qla,qla_backward",
                     help="comma-separated legs to run (stage1 always runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device copy (a kernel of known traffic for scaling HBM counters)")
@@ -344,6 +346,29 @@ def main() -> None:
                                 note="state stream: X read once (2d bytes per item); the finishing kernel is O(B S d)")
         res[leg] = {"value": ips, "unit": "items/s", "ms_per_step": ms, "ms_per_step_median": med,
                     "config": {"workload": f"stage-1 jagged batch, attn={leg}"}, "roofline": roof}
+    if "qla_backward" in legs:
+        dO = torch.randn((c1.B, c1.S, c1.d), device="cuda").to(torch.bfloat16)
+        dQ = torch.empty_like(dO)
+        dK, dV = torch.empty_like(xs[0]), torch.empty_like(xs[0])
+        wb = V.vista_qla_backward(xs[0], dev["off"], dev["Q"], dev["Wk"], dev["Wv"], dO, dQ, dK, dV, H=c1.H,
+                                  offsets_host=dev["off_host"])
+        kb = {"i": 0}
+
+        def stepb():
+            k = kb["i"] % SETS
+            kb["i"] += 1
+            V.vista_qla_backward(xs[k], dev["off"], dev["Q"], dev["Wk"], dev["Wv"], dO, dQ, dK, dV, H=c1.H,
+                                 offsets_host=dev["off_host"], workspace=wb)
+
+        ms, med = time_steps(stepb, a.steps, a.warmup)
+        ips = N / (ms * 1e-3)
+        res["qla_backward"] = {"value": ips, "unit": "items/s", "ms_per_step": ms, "ms_per_step_median": med,
+                               "config": {"workload": "stage-1 jagged batch, gradients of attn=qla (dQ, dK, dV)"},
+                               "roofline": hbm_roofline(6 * c1.d, ips, cal, kernel="qla_bwd_items_mfma_kernel<128>",
+                                                        bytes_per_item=6 * c1.d,
+                                                        note="X read twice (state pass, item pass) would be 4d; the "
+                                                             "algorithmic count is X once + dK and dV written = 6d bytes per item")}
+        del dO, dQ, dK, dV, wb
     del xs, outs, ws
     torch.cuda.empty_cache()
 
@@ -372,6 +397,26 @@ def main() -> None:
                          "roofline": hbm_roofline(bytes_cand, cand_per_s, cal, traffic=traffic.get("attend_mfma"),
                                                   kernel="attend_mfma_kernel<8>", bytes_per_candidate=bytes_cand,
                                                   exp_per_candidate=c2.S * c2.H)}
+        if "stage2_q8" in legs:
+            codes = [torch.empty((c2.B, c2.S, c2.d), device="cuda", dtype=torch.int8) for _ in range(SETS)]
+            scl = [torch.empty((c2.B, c2.S, c2.H), device="cuda", dtype=torch.float32) for _ in range(SETS)]
+            for k in range(SETS):
+                V.vista_quantize_summaries(summs[k], codes[k], scl[k], H=c2.H)
+            qt = {"i": 0}
+
+            def stepq():
+                k = qt["i"] % SETS
+                qt["i"] += 1
+                V.vista_target_attend_q8(cands[k], codes[k], scl[k], outs2[k], H=c2.H)
+
+            msq, medq = time_steps(stepq, a.steps, a.warmup)
+            cps = c2.B * c2.C / (msq * 1e-3)
+            bq = 2 * c2.d * 2 + (c2.S * c2.d + 4 * c2.S * c2.H) / c2.C
+            res["stage2_q8"] = {"value": cps, "unit": "candidate scores/s", "ms_per_step": msq, "ms_per_step_median": medq,
+                                "config": {"workload": "stage-2 serving on int8 summaries (one scale per token and head)"},
+                                "roofline": hbm_roofline(bq, cps, cal, kernel="attend_mfma_kernel<8> (int8 slab)",
+                                                         bytes_per_candidate=bq)}
+            del codes, scl
         del cands, summs, outs2
         torch.cuda.empty_cache()
 

@@ -114,11 +114,17 @@ __global__ __launch_bounds__(kThreads, (NKB <= 6 || NKB == 8) ? 3 : 2) void atte
   const int half = wave & 1;           // which 32 candidates of a round
   const int hf = lane >> 5, l32 = lane & 31;
   const int hgroups = p.H / kHeads;
-  int id = blockIdx.x;
-  const int chunk = id % p.chunks;
-  id /= p.chunks;
-  const int hg = id % hgroups;
-  const int b = id / hgroups;
+  // XCD-aware block -> (user, chunk, head group): block ids that differ by a multiple of 8 share an
+  // XCD and its L2, so the head groups of one (user, chunk) are placed 8 ids apart -- they read
+  // neighbouring halves of the same rows (of the same 128-byte lines when the summaries are int8).
+  const int64_t units = int64_t(p.B) * p.chunks;
+  const int64_t grp = blockIdx.x / (8 * hgroups);
+  const int idl = int(blockIdx.x - grp * (8 * hgroups));
+  const int64_t unit = grp * 8 + (idl & 7);
+  if (unit >= units) return;             // padding blocks of the last group (whole workgroup)
+  const int hg = idl >> 3;
+  const int chunk = int(unit % p.chunks);
+  const int b = int(unit / p.chunks);
   const int row_bytes = p.d * 2;
   const int slice = hg * (64 * kHeads);   // byte offset of this head group's channels inside a row
 
@@ -453,7 +459,8 @@ __global__ __launch_bounds__(kThreads, (NKB <= 6 || NKB == 8) ? 3 : 2) void atte
 
 template <int NKB>
 hipError_t launch_attend(const AttendParams& p, hipStream_t s) {
-  const unsigned blocks = unsigned(p.B) * unsigned(p.H / kHeads) * unsigned(p.chunks);
+  const int64_t units = int64_t(p.B) * p.chunks;
+  const unsigned blocks = unsigned((units + 7) / 8 * 8 * (p.H / kHeads));
   return launch(attend_mfma_kernel<NKB>, dim3(blocks), dim3(kThreads), 0, s, p);
 }
 
@@ -487,7 +494,7 @@ vista_status mfma_target_attend(const vista_attend_desc& d, float scale_log2, co
   while (per > 2 && groups * ((nrounds + per - 1) / per) < want) per >>= 1;
   p.rounds_per_wg = per;
   p.chunks = (nrounds + per - 1) / per;
-  if (groups * p.chunks > 0x7FFFFFFF) return VISTA_ERR_UNSUPPORTED;
+  if ((int64_t(d.B) * p.chunks + 7) / 8 * 8 * (d.H / kHeads) > 0x7FFFFFFF) return VISTA_ERR_UNSUPPORTED;
   hipError_t e;
   switch (nkb) {
     case 1: e = launch_attend<1>(p, s); break;

@@ -258,8 +258,10 @@ __global__ __launch_bounds__(256) void qla_finish_kernel(const float* __restrict
                                                          int seg, int64_t G, T* __restrict__ out,
                                                          const T* __restrict__ Q, int64_t q_user_stride,
                                                          const float* __restrict__ Ks,
-                                                         const float* __restrict__ Vs) {
+                                                         const float* __restrict__ Vs, int* status) {
   constexpr int kW = DH ? DH : kMaxDh;          // register rows are sized for it
+  // without a plan kernel in front (offsets checked on the host) the status word is cleared here
+  if (status && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) *status = VISTA_OK;
   __shared__ float z[kW * kW];
   const int dh = DH ? DH : d / H;
   const int b = blockIdx.x, h = blockIdx.y;
@@ -377,15 +379,40 @@ __global__ __launch_bounds__(256) void qla_bwd_state_kernel(const float* __restr
   int64_t g0 = begin / seg, g1 = (end - 1) / seg;
   if (g0 < 0) g0 = 0;
   if (g1 > G - 1) g1 = G - 1;
-  for (int e = threadIdx.x; e < zz; e += blockDim.x) {
-    float acc = 0.f;
-    for (int64_t g = g0; g <= g1; g += 8) {
-      float v[8];
+  // ascending-order sum of the user's records (a thread owns four neighbouring entries, eight
+  // 16-byte loads in flight), then SiLU'(Zs) and G^T
+  if (zz % 4 == 0) {
+    for (int e = 4 * threadIdx.x; e < zz; e += 4 * blockDim.x) {
+      float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+      for (int64_t g = g0; g <= g1; g += 8) {
+        float4 v[8];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) v[u] = g + u <= g1 ? partials[((g + u + b) * H + h) * zz + e] : 0.f;
+        for (int u = 0; u < 8; ++u)
+          v[u] = g + u <= g1 ? *reinterpret_cast<const float4*>(partials + ((g + u + b) * H + h) * zz + e)
+                             : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-      for (int u = 0; u < 8; ++u) acc += v[u];
+        for (int u = 0; u < 8; ++u) {
+          acc.x += v[u].x;
+          acc.y += v[u].y;
+          acc.z += v[u].z;
+          acc.w += v[u].w;
+        }
+      }
+      zs[e] = acc.x;
+      zs[e + 1] = acc.y;
+      zs[e + 2] = acc.z;
+      zs[e + 3] = acc.w;
     }
+  } else {
+    for (int e = threadIdx.x; e < zz; e += blockDim.x) {
+      float acc = 0.f;
+      for (int64_t g = g0; g <= g1; ++g) acc += partials[((g + b) * H + h) * zz + e];
+      zs[e] = acc;
+    }
+  }
+  __syncthreads();
+  for (int e = threadIdx.x; e < zz; e += blockDim.x) {
+    const float acc = zs[e];
     zs[e] = silu_prime_f(acc);
     gt[(e % dh) * (dh + 1) + e / dh] = silu_f(acc);
   }
@@ -538,10 +565,12 @@ static vista_status generic_summarize_t(const SummarizeArgs& a) {
   T* out = static_cast<T*>(a.out);
   if (qla && d.d / d.H == 32)
     VISTA_LAUNCH((qla_finish_kernel<T, 32>), dim3(d.B, d.H, (d.S + 63) / 64), dim3(256), 0, a.stream, partials, a.offsets, d.S, d.d,
-                 d.H, a.seg, a.G, out, Q, d.q_user_stride, Ks, Vs);
+                 d.H, a.seg, a.G, out, Q, d.q_user_stride, Ks, Vs,
+                 a.seg_user ? nullptr : reinterpret_cast<int*>(a.workspace));
   else if (qla)
     VISTA_LAUNCH((qla_finish_kernel<T, 0>), dim3(d.B, d.H, (d.S + 63) / 64), dim3(256), 0, a.stream, partials, a.offsets, d.S, d.d,
-                 d.H, a.seg, a.G, out, Q, d.q_user_stride, Ks, Vs);
+                 d.H, a.seg, a.G, out, Q, d.q_user_stride, Ks, Vs,
+                 a.seg_user ? nullptr : reinterpret_cast<int*>(a.workspace));
   else if (silu)
     VISTA_LAUNCH((merge_kernel<T, true>), dim3(d.B, d.H), dim3(256), 0, a.stream, partials, a.offsets, d.S, d.d,
                  d.H, a.seg, a.G, out, Q, d.q_user_stride, Ks, Vs, score_scale);

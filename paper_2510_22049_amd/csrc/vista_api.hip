@@ -172,6 +172,10 @@ static vista_status summarize_impl(const vista_summarize_desc* desc, const void*
     a.seg_user = nullptr;
     return mfma_summarize(a);
   }
+  if (offsets_host && mfma_qla_supported(*desc)) {     // likewise; the finishing kernel clears the status word
+    a.seg_user = nullptr;
+    return generic_summarize(a);
+  }
   int* seg_user = reinterpret_cast<int*>(a.workspace + kHeaderBytes);
   a.seg_user = seg_user;
   if (launch_plan(offsets, desc->B, desc->total_items, a.seg, a.G, reinterpret_cast<int*>(workspace), seg_user,
