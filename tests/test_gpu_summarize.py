@@ -184,3 +184,30 @@ def test_degenerate_batches(d, H, S):
     assert np.all(got[0] == 0) and np.all(got[2] == 0)
     assert_blocks_close(got[1:2], want[1:2], "bf16", "one item")
     assert np.all(got[1] == got[1][0])          # a single item: every query returns its value row
+
+
+def test_nothing_is_written_outside_out_and_the_stated_workspace():
+    """Canary bytes before and after `out` and after the workspace's stated size survive the call
+    (jagged users, several segments, both kernel families)."""
+    for d, H, S, dtype in ((128, 4, 256, "bf16"), (64, 2, 24, "f32")):
+        g = np.random.default_rng(71)
+        lens = [700, 0, 33, 1300]
+        off = I.offsets_from_lengths(lens)
+        r = lambda shape, s=1.0: I.round_to((g.normal(size=shape) * s).astype(np.float32), dtype)
+        X, Q, Wk, Wv = r((off[-1], d)), r((S, d)), r((d, d), d ** -0.5), r((d, d), d ** -0.5)
+        tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+        esz = 2 if dtype == "bf16" else 4
+        pad = 4096
+        n_out = len(lens) * S * d * esz
+        raw = torch.full((pad + n_out + pad,), 0xA5, dtype=torch.uint8, device="cuda")
+        out = raw[pad:pad + n_out].view(tdt).view(len(lens), S, d)
+        desc = V.summarize_desc(len(lens), S, d, H, V.VISTA_BF16 if dtype == "bf16" else V.VISTA_F32, int(off[-1]),
+                                segment_items=128)
+        need = V.vista_summarize_workspace_bytes(desc)
+        wraw = torch.full((need + pad,), 0x5A, dtype=torch.uint8, device="cuda")
+        V.vista_summarize(dev(X, dtype), torch.from_numpy(off).cuda(), dev(Q, dtype), dev(Wk, dtype), dev(Wv, dtype), out,
+                          H=H, segment_items=128, workspace=wraw[:need], offsets_host=torch.from_numpy(off))
+        torch.cuda.synchronize()
+        assert bool((raw[:pad] == 0xA5).all()) and bool((raw[pad + n_out:] == 0xA5).all()), "write outside out"
+        assert bool((wraw[need:] == 0x5A).all()), "write beyond the stated workspace size"
+        assert_blocks_close(host64(out), O.summarize(X, off, Q, Wk, Wv, H), dtype, "canary case")
