@@ -73,6 +73,9 @@ __global__ __launch_bounds__(D * 2, 2) void qla_state_mfma_kernel(QlaParams p) {
   constexpr int KS = D / 16;             // k-slices of a projection
   constexpr int CPT = kTile * CH / NT;   // X chunks a thread moves per tile (= 8)
   static_assert(kTile * CH % NT == 0, "tile must split evenly over the workgroup");
+  // At D = 256 the weights take half of the register file: scheduling fences keep the compiler from
+  // hoisting (and holding) operand reads; at D = 128 there is room and it may interleave freely.
+  constexpr bool kFence = D > 128;
   __shared__ uint4 xbuf[kRing][CH * 32];   // X tiles: [16-byte chunk][item]
 
   const int tid = threadIdx.x;
@@ -167,7 +170,7 @@ __global__ __launch_bounds__(D * 2, 2) void qla_state_mfma_kernel(QlaParams p) {
         Pack8 x;
         x.u = xbuf[xb][(2 * ks + hf) * 32 + l32];
         ak = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x.v, wk[ks], ak, 0, 0, 0);
-        if (ks % 4 == 3) __builtin_amdgcn_sched_barrier(0);   // keeps later operand reads from being hoisted and held
+        if (kFence && ks % 4 == 3) __builtin_amdgcn_sched_barrier(0);   // keeps later operand reads from being hoisted and held
       }
 #pragma unroll
       for (int i = 0; i < 16; i += 2) {
@@ -181,7 +184,7 @@ __global__ __launch_bounds__(D * 2, 2) void qla_state_mfma_kernel(QlaParams p) {
         if (i < 8) a0.w[i / 2] = pa; else a1.w[(i - 8) / 2] = pa;
       }
     }
-    __builtin_amdgcn_sched_barrier(0);
+    if (kFence) __builtin_amdgcn_sched_barrier(0);
     {
       f32x16 av = {0};
 #pragma unroll
@@ -189,7 +192,7 @@ __global__ __launch_bounds__(D * 2, 2) void qla_state_mfma_kernel(QlaParams p) {
         Pack8 x;
         x.u = xbuf[xb][(2 * ks + hf) * 32 + l32];
         av = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x.v, wv[ks], av, 0, 0, 0);
-        if (ks % 4 == 3) __builtin_amdgcn_sched_barrier(0);
+        if (kFence && ks % 4 == 3) __builtin_amdgcn_sched_barrier(0);
       }
 #pragma unroll
       for (int i = 0; i < 16; i += 2) {

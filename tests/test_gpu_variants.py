@@ -298,3 +298,32 @@ def test_qla_backward(dtype, d, H, S, per_user, seg):
             for name, got_, want_ in (("dK", gK[sl], wK[sl]), ("dV", gV[sl], wV[sl])):
                 err = block_errors(got_[None], want_[None])[0]
                 assert err <= tol, f"qla backward {name} user {b}: {err:.3e} > {tol:.0e}"
+
+
+@pytest.mark.parametrize("form", ["silu", "qla"])
+@pytest.mark.parametrize("d,H,S,dtype", [(128, 4, 256, "bf16"), (64, 2, 24, "f32")])
+def test_degenerate_batches_of_the_further_forms(form, d, H, S, dtype):
+    """No items at all (every user empty), and a batch whose only content is one item."""
+    g = np.random.default_rng(81)
+    r = lambda shape, s=1.0: I.round_to((g.normal(size=shape) * s).astype(np.float32), dtype)
+    Q, Wk, Wv = r((S, d)), r((d, d), d ** -0.5), r((d, d), d ** -0.5)
+    got = run(form, np.zeros((0, d), np.float32), np.array([0, 0, 0, 0]), Q, Wk, Wv, H, dtype)
+    assert got.shape == (3, S, d) and np.all(got == 0)
+    X = r((1, d))
+    got = run(form, X, np.array([0, 0, 1, 1]), Q, Wk, Wv, H, dtype, self_term=True)
+    want = oracle(form, X, np.array([0, 0, 1, 1]), Q, Wk, Wv, H, True)
+    assert np.all(got[0] == 0) and np.all(got[2] == 0)
+    assert_blocks_close(got[1:2], want[1:2], dtype, f"{form}: one item")
+
+
+def test_qla_backward_without_any_items():
+    d, H, S = 128, 4, 64
+    g = np.random.default_rng(82)
+    r = lambda shape, s=1.0: I.round_to((g.normal(size=shape) * s).astype(np.float32), "bf16")
+    Q, Wk, Wv, dO = r((S, d)), r((d, d), d ** -0.5), r((d, d), d ** -0.5), r((2, S, d))
+    dQ = torch.full((2, S, d), float("nan"), device="cuda", dtype=torch.bfloat16)
+    empty = torch.zeros((0, d), device="cuda", dtype=torch.bfloat16)
+    V.vista_qla_backward(empty, torch.zeros(3, dtype=torch.int64, device="cuda"), dev(Q, "bf16"), dev(Wk, "bf16"),
+                         dev(Wv, "bf16"), dev(dO, "bf16"), dQ, empty, empty, H=H)
+    torch.cuda.synchronize()
+    assert bool((dQ == 0).all())
