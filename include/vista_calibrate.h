@@ -34,8 +34,12 @@ enum {
   VISTA_CAL_MFMA_AGPR_ADD32 = 12, /* as MFMA_ADD32 with the accumulators in AGPRs        */
   VISTA_CAL_MFMA4 = 13,       /* 16 v_mfma_f32_4x4x4_16b_bf16 on four accumulators       */
   VISTA_CAL_MFMA4_ADD32 = 14, /* 16 of those + 32 v_add_f32                              */
-  VISTA_CAL_TILE_BODY = 15    /* two query blocks of the stage-1 tile loop, registers only; per
+  VISTA_CAL_TILE_BODY = 15,   /* two query blocks of the stage-1 tile loop, registers only; per
                                  block 6 MFMAs, 16 v_exp_f32, 8 v_cvt_pk_bf16_f32, 4 4x4x4 MFMAs */
+  VISTA_CAL_TILE_BODY_NOSMALL = 16, /* the same without the 4x4x4 MFMAs                       */
+  VISTA_CAL_TILE_BODY_NOPROJ = 17,  /* the same without the two projection MFMAs per block    */
+  VISTA_CAL_TILE_BODY_LOOSE = 18    /* the same instructions with the MFMA -> v_exp_f32 dependency
+                                       removed and the pack -> MFMA dependency one block long */
 };
 
 /*

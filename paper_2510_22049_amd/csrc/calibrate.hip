@@ -46,6 +46,7 @@ __global__ void issue_kernel(float* sink, int iters, float seed) {
     b[i] = (__bf16)(seed - i);
   }
   uint32_t packed[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  uint32_t packed2[8] = {1, 1, 1, 1, 1, 1, 1, 1};
   bf16x8 qa = a, qb = b;
   float w[16];
 #pragma unroll
@@ -145,6 +146,62 @@ __global__ void issue_kernel(float* sink, int iters, float seed) {
       block(acc[0], acc[3], qa, qb);
       block(acc[3], acc[0], qb, qa);
     }
+    if constexpr (MODE >= VISTA_CAL_TILE_BODY_NOSMALL && MODE <= VISTA_CAL_TILE_BODY_LOOSE) {
+      // The same two query blocks with one ingredient taken out or one dependency loosened:
+      //   NOSMALL  no 4x4x4 denominator MFMAs;   NOPROJ  no projection MFMAs;
+      //   LOOSE    the same instructions, but the exponentials work on registers of their own
+      //            (not on the scores the MFMAs just produced) and the P.V and denominator
+      //            MFMAs take the packs made one block earlier.
+      constexpr bool SMALL = MODE != VISTA_CAL_TILE_BODY_NOSMALL;
+      constexpr bool PROJ = MODE != VISTA_CAL_TILE_BODY_NOPROJ;
+      constexpr bool LOOSE = MODE == VISTA_CAL_TILE_BODY_LOOSE;
+      auto block = [&](f32x16& sc, f32x16& nx, const bf16x8& qin, bf16x8& qout, uint32_t* pin, uint32_t* pout) __attribute__((always_inline)) {
+        const f32x16 z = {0};
+        if constexpr (LOOSE) {
+          nx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qin, nx, 0, 0, 0);
+        } else {
+          nx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qin, z, 0, 0, 0);
+        }
+        nx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, qin, nx, 0, 0, 0);
+        if constexpr (PROJ) {
+          acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[1], 0, 0, 0);
+          acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, a, acc[1], 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 16; i += 2) {
+          float e0, e1;
+          if constexpr (LOOSE) {
+            e0 = v[i] = __builtin_amdgcn_exp2f(v[i]);
+            e1 = v[i + 1] = __builtin_amdgcn_exp2f(v[i + 1]);
+          } else {
+            e0 = __builtin_amdgcn_exp2f(sc[i]);
+            e1 = __builtin_amdgcn_exp2f(sc[i + 1]);
+          }
+          f32x2 f = {e0, e1};
+          pout[i / 2] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
+        }
+        const uint32_t* pu = LOOSE ? pin : pout;
+        if constexpr (SMALL) {
+          const i16x4 a4 = {short(0x3F80), short(0x3F80), short(0x3F80), short(0x3F80)};
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            const i16x4 b4 = {short(pu[2 * k]), short(pu[2 * k] >> 16), short(pu[2 * k + 1]), short(pu[2 * k + 1] >> 16)};
+            small[k & 1] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(a4, b4, small[k & 1], 0, 0, 0);
+          }
+        }
+        union { bf16x8 v; uint32_t w[4]; } p0, p1;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          p0.w[k] = pu[k];
+          p1.w[k] = pu[4 + k];
+        }
+        acc[2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, p0.v, acc[2], 0, 0, 0);
+        acc[2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, p1.v, acc[2], 0, 0, 0);
+        qout = p1.v;
+      };
+      block(acc[0], acc[3], qa, qb, packed2, packed);
+      block(acc[3], acc[0], qb, qa, packed, packed2);
+    }
     if constexpr (MODE == VISTA_CAL_MFMA16) {
 #pragma unroll
       for (int k = 0; k < 4; ++k) small[k] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, small[k], 0, 0, 0);
@@ -169,7 +226,7 @@ __global__ void issue_kernel(float* sink, int iters, float seed) {
     for (int i = 0; i < 4; ++i) s += small[k][i];
   }
 #pragma unroll
-  for (int i = 0; i < 8; ++i) s += __uint_as_float(packed[i]);
+  for (int i = 0; i < 8; ++i) s += __uint_as_float(packed[i]) + __uint_as_float(packed2[i]);
   if (s == 12345.678f) sink[threadIdx.x] = s;   // never true for the seeds used; keeps the loop alive
 }
 
@@ -255,6 +312,9 @@ extern "C" int vista_calibrate_issue(int what, int waves_per_simd, int iters, fl
     case VISTA_CAL_MFMA4: e = run_issue<VISTA_CAL_MFMA4>(waves_per_simd, iters, sink, s); break;
     case VISTA_CAL_TILE_BODY: e = run_issue<VISTA_CAL_TILE_BODY>(waves_per_simd, iters, sink, s); break;
     case VISTA_CAL_MFMA4_ADD32: e = run_issue<VISTA_CAL_MFMA4_ADD32>(waves_per_simd, iters, sink, s); break;
+    case VISTA_CAL_TILE_BODY_NOSMALL: e = run_issue<VISTA_CAL_TILE_BODY_NOSMALL>(waves_per_simd, iters, sink, s); break;
+    case VISTA_CAL_TILE_BODY_NOPROJ: e = run_issue<VISTA_CAL_TILE_BODY_NOPROJ>(waves_per_simd, iters, sink, s); break;
+    case VISTA_CAL_TILE_BODY_LOOSE: e = run_issue<VISTA_CAL_TILE_BODY_LOOSE>(waves_per_simd, iters, sink, s); break;
     default: return 1;
   }
   return e == hipSuccess ? 0 : 2;
