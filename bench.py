@@ -333,7 +333,7 @@ def main() -> None:
     for leg, attn in (("silu", V.VISTA_ATTN_SILU), ("qla", V.VISTA_ATTN_QLA)):
         if leg not in legs:
             continue
-        d_ = V.summarize_desc(c1.B, c1.S, c1.d, c1.H, V.VISTA_BF16, N, attn=attn)
+        d_ = V.summarize_desc(c1.B, c1.S, c1.d, c1.H, V.VISTA_BF16, N, attn=attn, segment_items=a.segment_items)
         w_ = torch.empty(V.vista_summarize_workspace_bytes(d_), dtype=torch.uint8, device="cuda")
         ms, med = time_steps(lambda: step1(attn, w_), a.steps, a.warmup)
         ips = N / (ms * 1e-3)

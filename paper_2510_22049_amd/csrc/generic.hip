@@ -249,98 +249,145 @@ __global__ void qla_state_kernel(const float* __restrict__ K, const float* __res
   }
 }
 
-// out_h = SiLU(Q_h) SiLU(Z_h) with Z_h the ascending-order sum of the user's states;
-// the self term adds (SiLU(q) . SiLU(k')) v'.  grid (B, H, runs of 64 queries), Z staged in LDS.
+// out_h = SiLU(Q_h) SiLU(Z_h) with Z_h the fixed-order sum of the user's states;
+// the self term adds (SiLU(q) . SiLU(k')) v'.  grid (B, H), 1024 threads, Z staged in LDS.
 // DH = the head width when it is known at compile time (32: the matrix-core shapes), else 0.
 template <typename T, int DH>
-__global__ __launch_bounds__(256) void qla_finish_kernel(const float* __restrict__ partials,
+__global__ __launch_bounds__(1024) void qla_finish_kernel(const float* __restrict__ partials,
                                                          const int64_t* __restrict__ offsets, int S, int d, int H,
                                                          int seg, int64_t G, T* __restrict__ out,
                                                          const T* __restrict__ Q, int64_t q_user_stride,
                                                          const float* __restrict__ Ks,
                                                          const float* __restrict__ Vs, int* status) {
   constexpr int kW = DH ? DH : kMaxDh;          // register rows are sized for it
+  constexpr int kRun = 256;                     // queries per pass: four threads each at 1024 threads
+  constexpr int kDeep = 8;                      // record loads a thread keeps in flight
   // without a plan kernel in front (offsets checked on the host) the status word is cleared here
-  if (status && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) *status = VISTA_OK;
+  if (status && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *status = VISTA_OK;
   __shared__ float z[kW * kW];
   const int dh = DH ? DH : d / H;
   const int b = blockIdx.x, h = blockIdx.y;
   const int64_t begin = offsets[b], end = offsets[b + 1];
   T* dst = out + int64_t(b) * S * d + h * dh;
   if (end <= begin) {
-    if (blockIdx.z == 0)
-      for (int e = threadIdx.x; e < S * dh; e += blockDim.x) store_as(dst + int64_t(e / dh) * d + (e % dh), 0.f);
+    for (int e = threadIdx.x; e < S * dh; e += blockDim.x) store_as(dst + int64_t(e / dh) * d + (e % dh), 0.f);
     return;
   }
   int64_t g0 = begin / seg, g1 = (end - 1) / seg;
   if (g0 < 0) g0 = 0;
   if (g1 > G - 1) g1 = G - 1;
-  // ascending-order sum of the user's records; a thread owns four neighbouring entries and keeps
-  // eight 16-byte loads in flight, so a long user is not a chain of dependent round trips
+  // Sum of the user's records in a fixed order: four groups of 256 threads take every fourth
+  // record each, ascending, a thread owning four neighbouring entries with eight 16-byte loads
+  // in flight (a long user is not a chain of dependent round trips); the four sub-sums are then
+  // added as ((s0 + s1) + s2) + s3.  The order depends on nothing but the record count.
   const int zz = dh * dh;
-  if (zz % 4 == 0) {
-    for (int e = 4 * threadIdx.x; e < zz; e += 4 * blockDim.x) {
+  if (zz % 4 == 0 && blockDim.x == 1024) {
+    const int grp = threadIdx.x >> 8, t256 = threadIdx.x & 255;
+    for (int e0 = 0; e0 < zz; e0 += 1024) {
+      const int e = e0 + 4 * t256;
       float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-      for (int64_t g = g0; g <= g1; g += 8) {
-        float4 v[8];
+      if (e < zz) {
+        for (int64_t g = g0 + grp; g <= g1; g += 4 * kDeep) {
+          float4 v[kDeep];
 #pragma unroll
-        for (int u = 0; u < 8; ++u)
-          v[u] = g + u <= g1 ? *reinterpret_cast<const float4*>(partials + ((g + u + b) * H + h) * zz + e)
-                             : make_float4(0.f, 0.f, 0.f, 0.f);
+          for (int u = 0; u < kDeep; ++u)
+            v[u] = g + 4 * u <= g1 ? *reinterpret_cast<const float4*>(partials + ((g + 4 * u + b) * H + h) * zz + e)
+                                   : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          acc.x += v[u].x;
-          acc.y += v[u].y;
-          acc.z += v[u].z;
-          acc.w += v[u].w;
+          for (int u = 0; u < kDeep; ++u) {
+            acc.x += v[u].x;
+            acc.y += v[u].y;
+            acc.z += v[u].z;
+            acc.w += v[u].w;
+          }
         }
       }
-      z[e] = acc.x / (1.f + expf(-acc.x));
-      z[e + 1] = acc.y / (1.f + expf(-acc.y));
-      z[e + 2] = acc.z / (1.f + expf(-acc.z));
-      z[e + 3] = acc.w / (1.f + expf(-acc.w));
+      for (int turn = 0; turn < 4; ++turn) {
+        if (grp == turn && e < zz) {
+          if (turn == 0) {
+            z[e] = acc.x; z[e + 1] = acc.y; z[e + 2] = acc.z; z[e + 3] = acc.w;
+          } else {
+            z[e] += acc.x; z[e + 1] += acc.y; z[e + 2] += acc.z; z[e + 3] += acc.w;
+          }
+        }
+        __syncthreads();
+      }
     }
   } else {
     for (int e = threadIdx.x; e < zz; e += blockDim.x) {
       float acc = 0.f;
       for (int64_t g = g0; g <= g1; ++g) acc += partials[((g + b) * H + h) * zz + e];
-      z[e] = acc / (1.f + expf(-acc));
+      z[e] = acc;
     }
+    __syncthreads();
+  }
+  for (int e = threadIdx.x; e < zz; e += blockDim.x) {
+    const float v = z[e];
+    z[e] = v / (1.f + expf(-v));
   }
   __syncthreads();
   const int64_t srow0 = q_user_stride ? int64_t(b) * S : 0;
-  // A block takes a run of 64 queries: their activated rows go to LDS (coalesced reads), then
-  // one query per thread walks the channels in a rolled loop -- a row of the state per step,
-  // read as a broadcast -- with the 32 or 64 outputs in registers.
-  __shared__ float qs[64][kW + 1];
-  const int i0 = blockIdx.z * 64;
-  for (int e = threadIdx.x; e < 64 * dh; e += blockDim.x) {
-    const int r = e / dh, a = e % dh;
-    float qa = 0.f;
-    if (i0 + r < S) qa = to_f32(Q[q_user_stride * b + int64_t(i0 + r) * d + h * dh + a]);
-    qs[r][a] = qa / (1.f + expf(-qa));
-  }
-  __syncthreads();
-  const int i = i0 + threadIdx.x;
-  if (i < S && threadIdx.x < 64) {
-    float o[kW];
+  // Queries in runs of kRun: their activated rows go to LDS (coalesced reads), then a thread
+  // walks the channels of one query in a rolled loop -- a row of the state per step -- with its
+  // quarter of the outputs in registers (four threads per query).
+  __shared__ float qs[kRun][kW + 1];
+  const int qi = threadIdx.x % kRun, quarter = threadIdx.x / kRun;
+  constexpr int kQ = (kW + 3) / 4;
+  const int cq = (dh + 3) / 4, c0 = quarter * cq;
+  for (int i0 = 0; i0 < S; i0 += kRun) {
+    __syncthreads();                     // the previous run's rows are no longer read
+    // (batches of eight elements per thread: the loads of a batch are all issued before the
+    // first is used, so a run costs one round trip to memory, not eight)
+    for (int e0 = threadIdx.x; e0 < kRun * dh; e0 += 8 * blockDim.x) {
+      float qv[8];
 #pragma unroll
-    for (int t = 0; t < kW; ++t) o[t] = 0.f;
-    float dot = 0.f;
-#pragma unroll 1
-    for (int a = 0; a < dh; ++a) {
-      const float pa = qs[threadIdx.x][a];
+      for (int j = 0; j < 8; ++j) {
+        const int e = e0 + j * blockDim.x;
+        const int r = e / dh, a = e % dh;
+        qv[j] = (e < kRun * dh && i0 + r < S) ? to_f32(Q[q_user_stride * b + int64_t(i0 + r) * d + h * dh + a]) : 0.f;
+      }
 #pragma unroll
-      for (int t = 0; t < kW; ++t)
-        if (t < dh) o[t] = fmaf(pa, z[a * dh + t], o[t]);
-      if (Ks) {
-        const float k = Ks[(srow0 + i) * d + h * dh + a];
-        dot = fmaf(pa, k / (1.f + expf(-k)), dot);
+      for (int j = 0; j < 8; ++j) {
+        const int e = e0 + j * blockDim.x;
+        if (e < kRun * dh) qs[e / dh][e % dh] = qv[j] / (1.f + expf(-qv[j]));
       }
     }
+    __syncthreads();
+    const int i = i0 + qi;
+    float o[kQ];
 #pragma unroll
-    for (int t = 0; t < kW; ++t)
-      if (t < dh) store_as(dst + int64_t(i) * d + t, Ks ? fmaf(dot, Vs[(srow0 + i) * d + h * dh + t], o[t]) : o[t]);
+    for (int t = 0; t < kQ; ++t) o[t] = 0.f;
+    if (i < S && quarter < 4) {
+      float dot = 0.f;
+#pragma unroll 1
+      for (int a = 0; a < dh; ++a) {
+        const float pa = qs[qi][a];
+#pragma unroll
+        for (int t = 0; t < kQ; ++t)
+          if (t < cq && c0 + t < dh) o[t] = fmaf(pa, z[a * dh + c0 + t], o[t]);
+        if (Ks) {
+          const float k = Ks[(srow0 + i) * d + h * dh + a];
+          dot = fmaf(pa, k / (1.f + expf(-k)), dot);
+        }
+      }
+      if (Ks) {
+#pragma unroll
+        for (int t = 0; t < kQ; ++t)
+          if (t < cq && c0 + t < dh) o[t] = fmaf(dot, Vs[(srow0 + i) * d + h * dh + c0 + t], o[t]);
+      }
+    }
+    // the run's outputs go back through LDS so that neighbouring lanes store neighbouring channels
+    __syncthreads();
+    if (i < S && quarter < 4) {
+#pragma unroll
+      for (int t = 0; t < kQ; ++t)
+        if (t < cq && c0 + t < dh) qs[qi][c0 + t] = o[t];
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < kRun * dh; e += blockDim.x) {
+      const int r = e / dh, a = e % dh;
+      if (i0 + r < S) store_as(dst + int64_t(i0 + r) * d + a, qs[r][a]);
+    }
   }
 }
 
@@ -351,12 +398,12 @@ __device__ __forceinline__ float silu_prime_f(float x) {
   return sg * (1.f + x * (1.f - sg));
 }
 
-// Per (user, head): the state Zs (ascending-order sum of the user's records), G = SiLU(Zs),
+// Per (user, head): the state Zs (fixed-order sum of the user's records), G = SiLU(Zs),
 //   dQ = (dO G^T) * SiLU'(Q)         written to d_queries,
 //   dZs = (SiLU(Q)^T dO) * SiLU'(Zs) written to dz [B][H][dh][dh] fp32 for the item pass.
-// grid (B, H), 256 threads; queries pass through LDS in runs of 64.
+// grid (B, H), 1024 threads; queries pass through LDS in runs of 64.
 template <typename T>
-__global__ __launch_bounds__(256) void qla_bwd_state_kernel(const float* __restrict__ partials,
+__global__ __launch_bounds__(1024) void qla_bwd_state_kernel(const float* __restrict__ partials,
                                                             const int64_t* __restrict__ offsets, int S, int d, int H,
                                                             int seg, int64_t G, const T* __restrict__ Q,
                                                             int64_t q_user_stride, const T* __restrict__ dO,
@@ -379,29 +426,41 @@ __global__ __launch_bounds__(256) void qla_bwd_state_kernel(const float* __restr
   int64_t g0 = begin / seg, g1 = (end - 1) / seg;
   if (g0 < 0) g0 = 0;
   if (g1 > G - 1) g1 = G - 1;
-  // ascending-order sum of the user's records (a thread owns four neighbouring entries, eight
-  // 16-byte loads in flight), then SiLU'(Zs) and G^T
-  if (zz % 4 == 0) {
-    for (int e = 4 * threadIdx.x; e < zz; e += 4 * blockDim.x) {
+  // The user's records, summed in the forward finishing kernel's order: four groups of 256
+  // threads take every fourth record each, ascending (a thread owns four neighbouring entries,
+  // eight 16-byte loads in flight), and the sub-sums are added as ((s0 + s1) + s2) + s3; then
+  // SiLU'(Zs) and G^T.
+  if (zz % 4 == 0 && blockDim.x == 1024) {
+    const int grp = threadIdx.x >> 8, t256 = threadIdx.x & 255;
+    for (int e0 = 0; e0 < zz; e0 += 1024) {
+      const int e = e0 + 4 * t256;
       float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-      for (int64_t g = g0; g <= g1; g += 8) {
-        float4 v[8];
+      if (e < zz) {
+        for (int64_t g = g0 + grp; g <= g1; g += 32) {
+          float4 v[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u)
-          v[u] = g + u <= g1 ? *reinterpret_cast<const float4*>(partials + ((g + u + b) * H + h) * zz + e)
-                             : make_float4(0.f, 0.f, 0.f, 0.f);
+          for (int u = 0; u < 8; ++u)
+            v[u] = g + 4 * u <= g1 ? *reinterpret_cast<const float4*>(partials + ((g + 4 * u + b) * H + h) * zz + e)
+                                   : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          acc.x += v[u].x;
-          acc.y += v[u].y;
-          acc.z += v[u].z;
-          acc.w += v[u].w;
+          for (int u = 0; u < 8; ++u) {
+            acc.x += v[u].x;
+            acc.y += v[u].y;
+            acc.z += v[u].z;
+            acc.w += v[u].w;
+          }
         }
       }
-      zs[e] = acc.x;
-      zs[e + 1] = acc.y;
-      zs[e + 2] = acc.z;
-      zs[e + 3] = acc.w;
+      for (int turn = 0; turn < 4; ++turn) {
+        if (grp == turn && e < zz) {
+          if (turn == 0) {
+            zs[e] = acc.x; zs[e + 1] = acc.y; zs[e + 2] = acc.z; zs[e + 3] = acc.w;
+          } else {
+            zs[e] += acc.x; zs[e + 1] += acc.y; zs[e + 2] += acc.z; zs[e + 3] += acc.w;
+          }
+        }
+        __syncthreads();
+      }
     }
   } else {
     for (int e = threadIdx.x; e < zz; e += blockDim.x) {
@@ -409,14 +468,14 @@ __global__ __launch_bounds__(256) void qla_bwd_state_kernel(const float* __restr
       for (int64_t g = g0; g <= g1; ++g) acc += partials[((g + b) * H + h) * zz + e];
       zs[e] = acc;
     }
+    __syncthreads();
   }
-  __syncthreads();
   for (int e = threadIdx.x; e < zz; e += blockDim.x) {
     const float acc = zs[e];
     zs[e] = silu_prime_f(acc);
     gt[(e % dh) * (dh + 1) + e / dh] = silu_f(acc);
   }
-  // this thread's entries of dG = SiLU(Q)^T dO: e = threadIdx.x + 256 k
+  // this thread's entries of dG = SiLU(Q)^T dO: e = threadIdx.x + blockDim.x k
   float dg[kMaxDh * kMaxDh / 256];
 #pragma unroll
   for (int k = 0; k < kMaxDh * kMaxDh / 256; ++k) dg[k] = 0.f;
@@ -432,7 +491,7 @@ __global__ __launch_bounds__(256) void qla_bwd_state_kernel(const float* __restr
     __syncthreads();
 #pragma unroll
     for (int k = 0; k < kMaxDh * kMaxDh / 256; ++k) {
-      const int e = threadIdx.x + 256 * k;
+      const int e = threadIdx.x + int(blockDim.x) * k;
       if (e < zz) {
         const int a = e / dh, c = e % dh;
         float acc = dg[k];
@@ -453,7 +512,7 @@ __global__ __launch_bounds__(256) void qla_bwd_state_kernel(const float* __restr
   }
 #pragma unroll
   for (int k = 0; k < kMaxDh * kMaxDh / 256; ++k) {
-    const int e = threadIdx.x + 256 * k;
+    const int e = threadIdx.x + int(blockDim.x) * k;
     if (e < zz) dzb[e] = dg[k] * zs[e];
   }
 }
@@ -564,11 +623,11 @@ static vista_status generic_summarize_t(const SummarizeArgs& a) {
   }
   T* out = static_cast<T*>(a.out);
   if (qla && d.d / d.H == 32)
-    VISTA_LAUNCH((qla_finish_kernel<T, 32>), dim3(d.B, d.H, (d.S + 63) / 64), dim3(256), 0, a.stream, partials, a.offsets, d.S, d.d,
+    VISTA_LAUNCH((qla_finish_kernel<T, 32>), dim3(d.B, d.H), dim3(1024), 0, a.stream, partials, a.offsets, d.S, d.d,
                  d.H, a.seg, a.G, out, Q, d.q_user_stride, Ks, Vs,
                  a.seg_user ? nullptr : reinterpret_cast<int*>(a.workspace));
   else if (qla)
-    VISTA_LAUNCH((qla_finish_kernel<T, 0>), dim3(d.B, d.H, (d.S + 63) / 64), dim3(256), 0, a.stream, partials, a.offsets, d.S, d.d,
+    VISTA_LAUNCH((qla_finish_kernel<T, 0>), dim3(d.B, d.H), dim3(1024), 0, a.stream, partials, a.offsets, d.S, d.d,
                  d.H, a.seg, a.G, out, Q, d.q_user_stride, Ks, Vs,
                  a.seg_user ? nullptr : reinterpret_cast<int*>(a.workspace));
   else if (silu)
@@ -618,7 +677,7 @@ static vista_status qla_backward_t(const SummarizeArgs& a, const void* d_out, vo
                    N, a.seg, a.seg_user, partials);
     }
   }
-  VISTA_LAUNCH(qla_bwd_state_kernel<T>, dim3(d.B, d.H), dim3(256), 0, a.stream, partials, a.offsets, d.S, d.d, d.H,
+  VISTA_LAUNCH(qla_bwd_state_kernel<T>, dim3(d.B, d.H), dim3(1024), 0, a.stream, partials, a.offsets, d.S, d.d, d.H,
                a.seg, a.G, static_cast<const T*>(a.Q), d.q_user_stride, static_cast<const T*>(d_out),
                static_cast<T*>(d_queries), dz);
   if (N > 0) {

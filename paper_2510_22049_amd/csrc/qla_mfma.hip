@@ -76,7 +76,10 @@ __global__ __launch_bounds__(D * 2, 2) void qla_state_mfma_kernel(QlaParams p) {
   // At D = 256 the weights take half of the register file: scheduling fences keep the compiler from
   // hoisting (and holding) operand reads; at D = 128 there is room and it may interleave freely.
   constexpr bool kFence = D > 128;
-  __shared__ uint4 xbuf[kRing][CH * 32];   // X tiles: [16-byte chunk][item]
+  // X tiles, row-major: chunk c of item r sits at position c ^ (r & 15) of the row, so a wave-wide
+  // direct load fetches four whole rows (1 KB of contiguous HBM) and the operand reads (lane = item,
+  // fixed chunk) still spread over all banks
+  __shared__ uint4 xbuf[kRing][CH * 32];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -118,10 +121,10 @@ __global__ __launch_bounds__(D * 2, 2) void qla_state_mfma_kernel(QlaParams p) {
     const char* base = reinterpret_cast<const char*>(p.X) + c.row * (D * 2);
 #pragma unroll
     for (int k = 0; k < CPT; ++k) {
-      const int slot = k * NT + tid;                      // LDS slot = chunk * 32 + item
-      int rel = slot & 31;
-      if (rel > last) rel = last;                         // rows past the piece repeat its last row
-      const uint32_t voff = uint32_t(rel) * (D * 2) + uint32_t(slot >> 5) * 16;
+      const int slot = k * NT + tid;                      // LDS slot = item * CH + position
+      const int r = slot / CH;
+      const int rel = r > last ? last : r;                // rows past the piece repeat its last row
+      const uint32_t voff = uint32_t(rel) * (D * 2) + uint32_t((slot % CH) ^ (r & 15)) * 16;
       const uint32_t lds_base = uint32_t(reinterpret_cast<uintptr_t>(
           (void __attribute__((address_space(3)))*)(&xbuf[xb][k * NT + wave * 64])));
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
@@ -168,18 +171,14 @@ __global__ __launch_bounds__(D * 2, 2) void qla_state_mfma_kernel(QlaParams p) {
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
         Pack8 x;
-        x.u = xbuf[xb][(2 * ks + hf) * 32 + l32];
+        x.u = xbuf[xb][l32 * CH + ((2 * ks + hf) ^ (l32 & 15))];
         ak = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x.v, wk[ks], ak, 0, 0, 0);
         if (kFence && ks % 4 == 3) __builtin_amdgcn_sched_barrier(0);   // keeps later operand reads from being hoisted and held
       }
 #pragma unroll
       for (int i = 0; i < 16; i += 2) {
-        float fa = ak[i] * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(ak[i]));
-        float fb = ak[i + 1] * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(ak[i + 1]));
-        if (last_in_piece) {                                // rows past the piece's end count for nothing
-          if (acc_row0(i) >= nvl) fa = 0.f;
-          if (acc_row0(i + 1) >= nvl) fb = 0.f;
-        }
+        const float fa = ak[i] * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(ak[i]));
+        const float fb = ak[i + 1] * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(ak[i + 1]));
         const uint32_t pa = cvt_pk_bf16(fa, fb);
         if (i < 8) a0.w[i / 2] = pa; else a1.w[(i - 8) / 2] = pa;
       }
@@ -190,7 +189,7 @@ __global__ __launch_bounds__(D * 2, 2) void qla_state_mfma_kernel(QlaParams p) {
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
         Pack8 x;
-        x.u = xbuf[xb][(2 * ks + hf) * 32 + l32];
+        x.u = xbuf[xb][l32 * CH + ((2 * ks + hf) ^ (l32 & 15))];
         av = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x.v, wv[ks], av, 0, 0, 0);
         if (kFence && ks % 4 == 3) __builtin_amdgcn_sched_barrier(0);
       }
@@ -198,6 +197,15 @@ __global__ __launch_bounds__(D * 2, 2) void qla_state_mfma_kernel(QlaParams p) {
       for (int i = 0; i < 16; i += 2) {
         const uint32_t pb = cvt_pk_bf16(av[i], av[i + 1]);
         if (i < 8) b0.w[i / 2] = pb; else b1.w[(i - 8) / 2] = pb;
+      }
+    }
+    if (last_in_piece) {
+      // Rows past the piece's end count for nothing: their SiLU(k) is cleared.  One wave-uniform
+      // branch per tile, taken once per piece, instead of a select per value on every tile.
+#pragma unroll
+      for (int i = 0; i < 16; i += 2) {
+        const uint32_t keep = (acc_row0(i) < nvl ? 0x0000FFFFu : 0u) | (acc_row0(i + 1) < nvl ? 0xFFFF0000u : 0u);
+        if (i < 8) a0.w[i / 2] &= keep; else a1.w[(i - 8) / 2] &= keep;
       }
     }
     z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0.v, b0.v, z, 0, 0, 0);
@@ -242,6 +250,7 @@ __global__ __launch_bounds__(D * 2, 2) void qla_bwd_items_mfma_kernel(QlaParams 
   constexpr int CH = D / 8;
   constexpr int KS = D / 16;
   constexpr int CPT = kTile * CH / NT;
+  constexpr bool kFence = D > 128;       // as in the forward kernel
   __shared__ uint4 xbuf[kRing][CH * 32];
 
   const int tid = threadIdx.x;
@@ -271,9 +280,9 @@ __global__ __launch_bounds__(D * 2, 2) void qla_bwd_items_mfma_kernel(QlaParams 
 #pragma unroll
     for (int k = 0; k < CPT; ++k) {
       const int slot = k * NT + tid;
-      int rel = slot & 31;
-      if (rel > last) rel = last;
-      const uint32_t voff = uint32_t(rel) * (D * 2) + uint32_t(slot >> 5) * 16;
+      const int r = slot / CH;
+      const int rel = r > last ? last : r;
+      const uint32_t voff = uint32_t(rel) * (D * 2) + uint32_t((slot % CH) ^ (r & 15)) * 16;
       const uint32_t lds_base = uint32_t(reinterpret_cast<uintptr_t>(
           (void __attribute__((address_space(3)))*)(&xbuf[xb][k * NT + wave * 64])));
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
@@ -335,9 +344,9 @@ __global__ __launch_bounds__(D * 2, 2) void qla_bwd_items_mfma_kernel(QlaParams 
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
           Pack8 x;
-          x.u = xbuf[xb][(2 * ks + hf) * 32 + l32];
+          x.u = xbuf[xb][l32 * CH + ((2 * ks + hf) ^ (l32 & 15))];
           ak = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wk[ks], x.v, ak, 0, 0, 0);
-          if (ks % 4 == 3) __builtin_amdgcn_sched_barrier(0);
+          if (kFence && ks % 4 == 3) __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
         for (int i = 0; i < 16; i += 2) {
@@ -354,15 +363,15 @@ __global__ __launch_bounds__(D * 2, 2) void qla_bwd_items_mfma_kernel(QlaParams 
           if (i < 8) pk0.w[i / 2] = w; else pk1.w[(i - 8) / 2] = w;
         }
       }
-      __builtin_amdgcn_sched_barrier(0);
+      if (kFence) __builtin_amdgcn_sched_barrier(0);
       {
         f32x16 av = {0};
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
           Pack8 x;
-          x.u = xbuf[xb][(2 * ks + hf) * 32 + l32];
+          x.u = xbuf[xb][l32 * CH + ((2 * ks + hf) ^ (l32 & 15))];
           av = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv[ks], x.v, av, 0, 0, 0);
-          if (ks % 4 == 3) __builtin_amdgcn_sched_barrier(0);
+          if (kFence && ks % 4 == 3) __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
         for (int i = 0; i < 16; i += 2) {
