@@ -110,7 +110,8 @@ def time_steps(fn, steps: int, warmup: int):
 CAL_MODES = {"exp16": 0, "add16": 1, "cvt8_add8": 2, "exp16_add16": 3, "mfma4": 4, "mfma4_add16": 5, "mfma4_add32": 6,
              "mfma4_add48": 7, "mfma4_add64": 8, "mfma4_exp16": 9, "mfma16x4": 10, "mfma16x4_add32": 11,
              "mfma4_agpr_add32": 12, "mfma4x4x4_16": 13, "mfma4x4x4_16_add32": 14, "tile_body2": 15,
-             "tile_body2_no_small": 16, "tile_body2_no_proj": 17, "tile_body2_loose_deps": 18}
+             "tile_body2_no_small": 16, "tile_body2_no_proj": 17, "tile_body2_loose_deps": 18,
+             "tile_body2_lds": 19, "tile_body2_lds_barrier": 20, "tile_body2_lds_barrier_publish": 21}
 
 
 def calibrate(full: bool):

@@ -38,8 +38,12 @@ enum {
                                  block 6 MFMAs, 16 v_exp_f32, 8 v_cvt_pk_bf16_f32, 4 4x4x4 MFMAs */
   VISTA_CAL_TILE_BODY_NOSMALL = 16, /* the same without the 4x4x4 MFMAs                       */
   VISTA_CAL_TILE_BODY_NOPROJ = 17,  /* the same without the two projection MFMAs per block    */
-  VISTA_CAL_TILE_BODY_LOOSE = 18    /* the same instructions with the MFMA -> v_exp_f32 dependency
+  VISTA_CAL_TILE_BODY_LOOSE = 18,   /* the same instructions with the MFMA -> v_exp_f32 dependency
                                        removed and the pack -> MFMA dependency one block long */
+  VISTA_CAL_TILE_BODY_LDS = 19,     /* TILE_BODY with five MFMA operands per block read from LDS
+                                       (ds_read_b128), as the kernel's projection and P.V have    */
+  VISTA_CAL_TILE_BODY_LDS_BAR = 20, /* ... plus an LDS-only workgroup barrier every four blocks   */
+  VISTA_CAL_TILE_BODY_LDS_BAR_PUB = 21 /* ... plus 8 packs and two ds_write_b128 every four blocks */
 };
 
 /*

@@ -202,6 +202,78 @@ __global__ void issue_kernel(float* sink, int iters, float seed) {
       block(acc[0], acc[3], qa, qb, packed2, packed);
       block(acc[3], acc[0], qb, qa, packed, packed2);
     }
+    if constexpr (MODE >= VISTA_CAL_TILE_BODY_LDS && MODE <= VISTA_CAL_TILE_BODY_LDS_BAR_PUB) {
+      // The two query blocks again, now with the traffic the kernel has around them:
+      //   LDS          the projection MFMAs take both operands from LDS (4 ds_read_b128 per block)
+      //                and the second P.V MFMA takes its A operand from LDS (1 per block);
+      //   LDS_BAR      plus one LDS-only workgroup barrier every four blocks (a tile);
+      //   LDS_BAR_PUB  plus, per tile, the publication of a projected tile: 8 packs of the
+      //                projection accumulator and two ds_write_b128.
+      constexpr bool BAR = MODE >= VISTA_CAL_TILE_BODY_LDS_BAR;
+      constexpr bool PUB = MODE == VISTA_CAL_TILE_BODY_LDS_BAR_PUB;
+      __shared__ uint4 lbuf[(10 + 2 * 16) * 64];   // ten operand slabs of 1 KB read by every wave + two per wave slot for publishing
+      const int lane = threadIdx.x & 63, slot = threadIdx.x >> 6;
+      uint4* mine = lbuf + lane;
+      uint4* pub = lbuf + (10 + 2 * slot) * 64 + lane;
+      if (it == 0) {
+        for (int k = slot; k < 10; k += blockDim.x >> 6) mine[k * 64] = make_uint4(0x3F803F80u, 0x3F003F00u, 0x3E803E80u, 0x3F803F80u);
+        __syncthreads();
+      }
+      auto block = [&](const f32x16& sc, f32x16& nx, const bf16x8& qin, bf16x8& qout, int half) __attribute__((always_inline)) {
+        const f32x16 z = {0};
+        nx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qin, z, 0, 0, 0);
+        nx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, qin, nx, 0, 0, 0);
+        union U { bf16x8 v; uint4 u; uint32_t w[4]; };
+        U x0, w0, x1, w1, vv;
+        x0.u = mine[(5 * half + 0) * 64];
+        w0.u = mine[(5 * half + 1) * 64];
+        x1.u = mine[(5 * half + 2) * 64];
+        w1.u = mine[(5 * half + 3) * 64];
+        vv.u = mine[(5 * half + 4) * 64];
+        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x0.v, w0.v, acc[1], 0, 0, 0);
+        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x1.v, w1.v, acc[1], 0, 0, 0);
+        U p0, p1;
+#pragma unroll
+        for (int i = 0; i < 16; i += 2) {
+          f32x2 f = {__builtin_amdgcn_exp2f(sc[i]), __builtin_amdgcn_exp2f(sc[i + 1])};
+          const uint32_t pk = __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
+          if (i < 8) p0.w[i / 2] = pk; else p1.w[(i - 8) / 2] = pk;
+        }
+        const i16x4 a4 = {short(0x3F80), short(0x3F80), short(0x3F80), short(0x3F80)};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const uint32_t w0_ = k < 2 ? p0.w[2 * k] : p1.w[2 * k - 4], w1_ = k < 2 ? p0.w[2 * k + 1] : p1.w[2 * k - 3];
+          const i16x4 b4 = {short(w0_), short(w0_ >> 16), short(w1_), short(w1_ >> 16)};
+          small[k & 1] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(a4, b4, small[k & 1], 0, 0, 0);
+        }
+        acc[2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, p0.v, acc[2], 0, 0, 0);
+        acc[2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vv.v, p1.v, acc[2], 0, 0, 0);
+        qout = p1.v;
+      };
+      block(acc[0], acc[3], qa, qb, 0);
+      block(acc[3], acc[0], qb, qa, 1);
+      if (it & 1) {                          // every four blocks: the end of a tile
+        if constexpr (PUB) {
+          union { uint4 u; uint32_t w[4]; } r0, r1;
+#pragma unroll
+          for (int i = 0; i < 16; i += 2) {
+            f32x2 f = {acc[1][i], acc[1][i + 1]};
+            const uint32_t pk = __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
+            if (i < 8) r0.w[i / 2] = pk; else r1.w[(i - 8) / 2] = pk;
+          }
+          pub[0] = r0.u;
+          pub[64] = r1.u;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) acc[1][i] = 0.f;
+        }
+        if constexpr (BAR) {
+          __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+          __builtin_amdgcn_s_barrier();
+          __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+        }
+      }
+      asm volatile("" ::: "memory");          // the buffer counts as changed: the operand reads stay in the loop
+    }
     if constexpr (MODE == VISTA_CAL_MFMA16) {
 #pragma unroll
       for (int k = 0; k < 4; ++k) small[k] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, small[k], 0, 0, 0);
@@ -315,6 +387,9 @@ extern "C" int vista_calibrate_issue(int what, int waves_per_simd, int iters, fl
     case VISTA_CAL_TILE_BODY_NOSMALL: e = run_issue<VISTA_CAL_TILE_BODY_NOSMALL>(waves_per_simd, iters, sink, s); break;
     case VISTA_CAL_TILE_BODY_NOPROJ: e = run_issue<VISTA_CAL_TILE_BODY_NOPROJ>(waves_per_simd, iters, sink, s); break;
     case VISTA_CAL_TILE_BODY_LOOSE: e = run_issue<VISTA_CAL_TILE_BODY_LOOSE>(waves_per_simd, iters, sink, s); break;
+    case VISTA_CAL_TILE_BODY_LDS: e = run_issue<VISTA_CAL_TILE_BODY_LDS>(waves_per_simd, iters, sink, s); break;
+    case VISTA_CAL_TILE_BODY_LDS_BAR: e = run_issue<VISTA_CAL_TILE_BODY_LDS_BAR>(waves_per_simd, iters, sink, s); break;
+    case VISTA_CAL_TILE_BODY_LDS_BAR_PUB: e = run_issue<VISTA_CAL_TILE_BODY_LDS_BAR_PUB>(waves_per_simd, iters, sink, s); break;
     default: return 1;
   }
   return e == hipSuccess ? 0 : 2;
