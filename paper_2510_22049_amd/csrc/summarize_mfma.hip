@@ -5,8 +5,8 @@
 //   1. the X tile (32 x D bf16) goes from HBM straight into LDS (direct
 //      global->LDS loads, three tiles deep, no stop in registers);
 //   2. wave "K" of a pair forms K_h^T = (scale*log2e W_k,h)^T X^T, wave "V" forms
-//      V_h = X W_v,h -- eight 32x32x16 MFMAs each for D = 128, weights read as
-//      LDS operands -- and both hand the bf16 result to their partner through LDS;
+//      V_h = X W_v,h -- eight 32x32x16 MFMAs each for D = 128, weights held in registers
+//      (as LDS operands at D = 256) -- and both hand the bf16 result to their partner through LDS;
 //   3. each wave owns half of the S queries: for every block of 32 queries
 //      S^T = K_h Q_h^T (items x queries), p = 2^(s - m), O^T += V_h^T P^T.
 // With items on the MFMA row index and queries on the column index, every lane
@@ -144,13 +144,17 @@ struct Int { static constexpr int value = V; };
 
 constexpr int kXBuf = 3;             // ring depth of the X tiles and of the projected tiles in LDS
 
+// Where a projecting wave keeps its 2 x (D x 32) weight operands: in registers at D = 128 (32 of
+// them; it saves half of the operand reads of a projection), in LDS at D = 256 (64 would not fit).
+__host__ __device__ constexpr bool weights_in_registers(int D) { return D == 128; }
+
 // Shared memory of one workgroup.
 template <int D, int HPW>
 struct SummarizeLds {
   uint4 xbuf[kXBuf][(D / 8) * 32];    // X tiles: [16-byte chunk][item], filled by direct global->LDS loads
   uint4 kvbuf[kXBuf][HPW][2][2][64];  // projected tiles: [ring slot][head][K|V][half of the 16 registers][lane]
   float knorm[kXBuf][HPW][64];        // squared norm of the scaled key rows (half per lane)
-  uint4 wop[HPW][2][D / 16][64];      // projection weights as MFMA operands: [head][K|V][k-slice][lane]
+  uint4 wop[weights_in_registers(D) ? 1 : HPW * 2 * (D / 16) * 64];   // projection weights as MFMA operands (D = 256): [head][K|V][k-slice][lane]
 };
 
 // Body of one wave; ROLE 0 forms K^T, ROLE 1 forms V, ROLE 2 forms nothing and only attends
@@ -184,11 +188,12 @@ __device__ __forceinline__ void summarize_wave(const MfmaSummarizeParams& p, Sum
   const int hf = lane >> 5;
   const int l32 = lane & 31;
 
-  // Projection weights of this wave's head as MFMA operands, parked in LDS (each
-  // wave reads back only what it wrote; they are off the critical path, so the
-  // registers go to the accumulators instead).  Element j of slice ks is
+  // Projection weights of this wave's head as MFMA operands, in registers or parked in LDS
+  // (each wave reads back only what it wrote).  Element j of slice ks is
   // W[16 ks + 8 hf + j][32 h + l32]; the key weights carry scale*log2(e), so the
   // scores leave the MFMA in base-2 units.
+  constexpr bool WREG = weights_in_registers(D);
+  bf16x8 wreg[WREG ? KS : 1];
   if constexpr (PROJ) {
     const uint16_t* W = ROLE ? p.Wv : p.Wk;
 #pragma unroll
@@ -199,7 +204,7 @@ __device__ __forceinline__ void summarize_wave(const MfmaSummarizeParams& p, Sum
         const uint16_t w = W[(16 * ks + 8 * hf + j) * D + 32 * h + l32];
         t.h[j] = ROLE ? w : f32_to_bf16_bits(__uint_as_float(uint32_t(w) << 16) * p.c);
       }
-      sm.wop[hl][WR][ks][lane] = t.u;
+      if constexpr (WREG) wreg[ks] = t.v; else sm.wop[((hl * 2 + WR) * KS + ks) * 64 + lane] = t.u;
     }
   }
 
@@ -304,7 +309,7 @@ __device__ __forceinline__ void summarize_wave(const MfmaSummarizeParams& p, Sum
       for (int ks = ks0; ks < ks1; ++ks) {
         Pack8 x, w;
         x.u = sm.xbuf[buf][(2 * ks + hf) * 32 + l32];
-        w.u = sm.wop[hl][WR][ks][lane];
+        if constexpr (WREG) w.v = wreg[ks]; else w.u = sm.wop[((hl * 2 + WR) * KS + ks) * 64 + lane];
         acc = ROLE ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(x.v, w.v, acc, 0, 0, 0)
                    : __builtin_amdgcn_mfma_f32_32x32x16_bf16(w.v, x.v, acc, 0, 0, 0);
       }
