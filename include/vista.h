@@ -95,9 +95,10 @@ typedef struct {
  * a segment is processed by one workgroup and is further cut at user
  * boundaries into pieces.  Piece (g, b) -- the rows of user b inside segment g
  * -- writes its running maximum, sum of exponentials and un-normalised output
- * to partial slot g + b; a merge pass combines a user's slots in ascending g.
- * The schedule is a pure function of (offsets, segment_items), never of the
- * device, so results are bitwise reproducible.
+ * to partial slot g + b; a merge pass combines a user's slots in an order fixed
+ * by their count alone (ascending g; the quasi-linear form adds four interleaved
+ * ascending sub-sums).  The schedule is a pure function of (offsets,
+ * segment_items), never of the device, so results are bitwise reproducible.
  *
  * vista_summarize_segment_items: the segment size the call will use
  * (desc->segment_items, or the default derived from total_items and the
