@@ -24,3 +24,11 @@ def test_more_than_one_gpu_is_refused(monkeypatch, capsys):
     with pytest.raises(SystemExit) as e:
         bench.main()
     assert "one GPU" in str(e.value)
+
+
+def test_calibration_modes_match_the_header():
+    """bench.py's table of loop bodies names every value of the header's enum, and nothing else."""
+    text = open(os.path.join(bench.ROOT, "include", "vista_calibrate.h")).read()
+    enum = {int(v) for v in re.findall(r"VISTA_CAL_[A-Z0-9_]+ = (\d+)", text)}
+    assert enum == set(bench.CAL_MODES.values())
+    assert len(bench.CAL_MODES) == len(enum) == max(enum) + 1
