@@ -100,3 +100,78 @@ def test_attend_and_ffn_reject_bad_arguments():
     assert L.vista_sglu_ffn(C.byref(f), one, one, one, one, one, None) == V.VISTA_ERR_UNSUPPORTED
     f = V.FfnDesc(rows=0, d=64, d_ff=64, dtype=V.VISTA_BF16, eps=0.0)
     assert L.vista_sglu_ffn(C.byref(f), one, one, one, one, one, None) == V.VISTA_ERR_SHAPE
+
+
+def test_forms_and_flags_are_validated():
+    L = V.lib()
+    one = C.c_void_p(256)
+    call = lambda d: L.vista_summarize(C.byref(d), one, one, None, one, one, one, one, one, 1 << 30, None)
+    assert call(desc(attn=3)) == V.VISTA_ERR_UNSUPPORTED             # no such form
+    assert call(desc(attn=-1)) == V.VISTA_ERR_UNSUPPORTED
+    d = desc()
+    d.flags = 2                                                       # unknown flag bit
+    assert call(d) == V.VISTA_ERR_SHAPE
+    d = desc()
+    d.reserved = 1
+    assert call(d) == V.VISTA_ERR_SHAPE
+    assert call(desc(attn=V.VISTA_ATTN_QLA, scale=0.5)) == V.VISTA_ERR_SHAPE   # the quasi-linear form has no score scale
+    # segment default of the quasi-linear form: four times finer
+    assert V.vista_summarize_segment_items(desc(total_items=768597, B=64, attn=V.VISTA_ATTN_QLA)) == 768
+
+
+def test_codec_entry_points_reject_bad_arguments():
+    L = V.lib()
+    one = C.c_void_p(256)
+    c = V.CodecDesc(rows=4, d=64, H=3, dtype=V.VISTA_BF16)
+    assert L.vista_quantize_summaries(C.byref(c), one, one, one, None) == V.VISTA_ERR_SHAPE
+    c = V.CodecDesc(rows=0, d=64, H=2, dtype=V.VISTA_BF16)
+    assert L.vista_quantize_summaries(C.byref(c), one, one, one, None) == V.VISTA_ERR_SHAPE
+    c = V.CodecDesc(rows=4, d=256, H=2, dtype=V.VISTA_BF16)            # heads wider than 64
+    assert L.vista_quantize_summaries(C.byref(c), one, one, one, None) == V.VISTA_ERR_UNSUPPORTED
+    c = V.CodecDesc(rows=4, d=64, H=2, dtype=V.VISTA_BF16)
+    assert L.vista_quantize_summaries(C.byref(c), one, None, one, None) == V.VISTA_ERR_NULL
+    assert L.vista_quantize_summaries(None, one, one, one, None) == V.VISTA_ERR_NULL
+    # summaries as codes: both the codes and their scales are required
+    a = V.AttendDesc(B=1, C=4, S=32, d=128, H=4, dtype=V.VISTA_BF16, scale=0.0)
+    assert L.vista_target_attend_q8(C.byref(a), one, None, one, one, None) == V.VISTA_ERR_NULL
+    assert L.vista_target_attend_q8(C.byref(a), one, one, None, one, None) == V.VISTA_ERR_NULL
+    a.flags = 4
+    assert L.vista_target_attend_q8(C.byref(a), one, one, one, one, None) == V.VISTA_ERR_SHAPE
+    # the fused codec exists for the matrix-core shapes only
+    d = desc(dtype=V.VISTA_F32)
+    st = L.vista_summarize_q8(C.byref(d), one, one, None, one, one, one, one, one, one, 1 << 30, None)
+    assert st == V.VISTA_ERR_UNSUPPORTED
+    d = V.summarize_desc(B=2, S=256, d=128, H=4, dtype=V.VISTA_BF16, total_items=100)
+    st = L.vista_summarize_q8(C.byref(d), one, one, None, one, one, one, one, None, one, 1 << 30, None)
+    assert st == V.VISTA_ERR_NULL
+
+
+def test_qla_backward_rejects_bad_arguments():
+    L = V.lib()
+    one = C.c_void_p(256)
+    args = lambda d, **kw: [C.byref(d)] + [kw.get(k, one) for k in
+                                            ("x", "off", "off_host", "q", "wk", "wv", "do", "dq", "dk", "dv", "ws")] + \
+        [kw.get("bytes", 1 << 30), None]
+    d = desc()                                                          # softmax form: no gradients here
+    assert L.vista_qla_backward(*args(d, off_host=None)) == V.VISTA_ERR_UNSUPPORTED
+    assert V.lib().vista_qla_backward_workspace_bytes(C.byref(d)) == 0
+    d = desc(attn=V.VISTA_ATTN_QLA)
+    assert L.vista_qla_backward(*args(d, off_host=None, do=None)) == V.VISTA_ERR_NULL
+    assert L.vista_qla_backward(*args(d, off_host=None, dk=None)) == V.VISTA_ERR_NULL
+    bad = np.array([0, 60, 50], dtype=np.int64)
+    assert L.vista_qla_backward(*args(d, off_host=bad.ctypes.data)) == V.VISTA_ERR_OFFSETS
+    good = np.array([0, 50, 100], dtype=np.int64)
+    need = L.vista_qla_backward_workspace_bytes(C.byref(d))
+    assert need > V.vista_summarize_workspace_bytes(d) > 0
+    assert L.vista_qla_backward(*args(d, off_host=good.ctypes.data, bytes=need - 1)) == V.VISTA_ERR_WORKSPACE
+    d.flags = V.VISTA_FLAG_SELF_TERM                                    # gradients of the self term are not built
+    assert L.vista_qla_backward(*args(d, off_host=good.ctypes.data)) == V.VISTA_ERR_UNSUPPORTED
+
+
+def test_static_entry_point_rejects_what_does_not_fit_its_array():
+    L = V.lib()
+    one = C.c_void_p(256)
+    d = V.summarize_desc(B=8, S=256, d=128, H=4, dtype=V.VISTA_BF16, total_items=8_000_000)   # needs ~180 MB
+    assert V.vista_summarize_workspace_bytes(d) > V.VISTA_STATIC_SCRATCH_BYTES
+    assert L.vista_summarize_static(C.byref(d), one, one, None, one, one, one, one, None) == V.VISTA_ERR_SCRATCH
+    assert L.vista_summarize_static(C.byref(desc(B=0)), one, one, None, one, one, one, one, None) == V.VISTA_ERR_SHAPE
