@@ -104,6 +104,32 @@ def test_config3_lifelong_all_users_sampled_queries():
               flush=True)
 
 
+@pytest.mark.parametrize("form", ["silu", "qla"])
+def test_config3_lifelong_further_forms(form):
+    """The lifelong shape (8 x 1,000,000 items, ~1000 segments per call) through the SiLU score
+    form and through quasi-linear attention: the first, a middle and the last user, 32 query rows
+    each (every output row of both forms depends on its own query only)."""
+    c = I.CONFIGS[3]
+    lens = I.lengths(c)
+    X, off = history_on_device(c, lens)
+    Q, Wk, Wv = I.virtual_queries(c), I.projection(c, "W_k"), I.projection(c, "W_v")
+    attn = V.VISTA_ATTN_SILU if form == "silu" else V.VISTA_ATTN_QLA
+    out = torch.full((c.B, c.S, c.d), float("nan"), device="cuda", dtype=torch.bfloat16)
+    ws = V.vista_summarize(X, torch.from_numpy(off).cuda(), dev(Q, "bf16"), dev(Wk, "bf16"), dev(Wv, "bf16"), out,
+                           H=c.H, offsets_host=torch.from_numpy(off), attn=attn)
+    torch.cuda.synchronize()
+    assert int(ws[:4].view(torch.int32).item()) == 0
+    assert bool(torch.isfinite(out.float()).all())
+    rows = spread_rows(c.S, 4)
+    got = host64(out[:, torch.from_numpy(rows).cuda()])
+    oracle = O.summarize_silu if form == "silu" else O.summarize_qla
+    for b in (0, 3, c.B - 1):
+        Xb = I.history_user(c, b, int(lens[b]))
+        want = oracle(Xb, [0, len(Xb)], Q[rows], Wk, Wv, c.H)
+        err = assert_blocks_close(got[b:b + 1], want, "bf16", f"config 3 {form} user {b}")
+        print(f"config 3 {form} user {b}: block error {err:.2e}", flush=True)
+
+
 def test_config5_end_to_end_sampled_users():
     """256 users, lengths U[10k, 100k], two stacked layers (d=256, 8 heads, S=512) with the gated
     block between, then 256 candidates per user.  Every call of the chain is checked against the
