@@ -327,3 +327,67 @@ def test_qla_backward_without_any_items():
                          dev(Wv, "bf16"), dev(dO, "bf16"), dQ, empty, empty, H=H)
     torch.cuda.synchronize()
     assert bool((dQ == 0).all())
+
+
+def random_lengths(g, seg):
+    """A seeded jagged batch whose users end on, just before and just after tile and segment
+    boundaries, with empty and single-item users mixed in."""
+    B = int(g.integers(1, 13))
+    kinds = g.integers(0, 5, size=B)
+    lens = []
+    for k in kinds:
+        if k == 0:
+            lens.append(int(g.integers(0, 3)))                              # empty, one or two items
+        elif k == 1:
+            lens.append(int(32 * g.integers(1, 6) + g.integers(-1, 2)))     # around a tile boundary
+        elif k == 2:
+            lens.append(int(seg * g.integers(1, 4) + g.integers(-2, 3)))    # around a segment boundary
+        else:
+            lens.append(int(g.integers(3, 900)))
+    if sum(lens) == 0:
+        lens[0] = 37
+    return lens
+
+
+@pytest.mark.parametrize("form", ["softmax", "silu", "qla"])
+@pytest.mark.parametrize("seed", range(6))
+def test_random_jagged_batches_on_the_matrix_core_paths(form, seed):
+    """Seeded random batches (user count, lengths at tile and segment edges, segment size, shape,
+    shared or per-user queries, self term) through the three forms."""
+    g = np.random.default_rng(1000 + seed)
+    seg = int(g.choice([32, 64, 96, 256, 992]))
+    d, H, S = [(128, 4, 256), (256, 8, 128), (128, 4, 64), (256, 8, 512)][seed % 4]
+    lens = random_lengths(g, seg)
+    per_user, self_term = bool(g.integers(0, 2)), bool(g.integers(0, 2))
+    X, off, Q, Wk, Wv = problem(2000 + seed, lens, d, S, "bf16", per_user=per_user)
+    got = run(form, X, off, Q, Wk, Wv, H, "bf16", self_term=self_term, segment_items=seg,
+              offsets_host=torch.from_numpy(off) if seed % 2 else None)
+    want = oracle(form, X, off, Q, Wk, Wv, H, self_term)
+    assert_blocks_close(got, want, "bf16", f"{form} seed={seed} lens={lens} seg={seg} d={d} S={S}")
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_stage2_shapes(seed):
+    """Seeded random stage-2 shapes on the matrix-core path: user and candidate counts that leave
+    ragged rounds and padding workgroups, every S the kernel takes, bf16 or int8 summaries, with
+    and without the self term, default or explicit scale."""
+    g = np.random.default_rng(3000 + seed)
+    d, H = [(128, 4), (256, 8)][seed % 2]
+    S = int(g.choice([32, 64, 96, 128, 160, 192, 224, 256, 320, 384, 448, 512]))
+    B, C = int(g.integers(1, 20)), int(g.integers(1, 600))
+    self_term, q8 = bool(g.integers(0, 2)), bool(g.integers(0, 2))
+    scale = [0.0, 0.11][int(g.integers(0, 2))]
+    bf = lambda x: I.round_to(np.asarray(x, dtype=np.float32), "bf16")
+    T, Y = bf(g.normal(size=(B, C, d))), bf(g.normal(size=(B, S, d)) * g.uniform(0.3, 2.0))
+    out = torch.full(T.shape, float("nan"), device="cuda", dtype=torch.bfloat16)
+    if q8:
+        wc, ws = O.quantize_summaries(Y, H)
+        Yref = O.dequantize_summaries(wc, ws)
+        V.vista_target_attend_q8(dev(T, "bf16"), torch.from_numpy(wc).cuda(), torch.from_numpy(ws).cuda(), out, H=H,
+                                 scale=scale, self_term=self_term)
+    else:
+        Yref = Y
+        V.vista_target_attend(dev(T, "bf16"), dev(Y, "bf16"), out, H=H, scale=scale, self_term=self_term)
+    torch.cuda.synchronize()
+    want = O.target_attend(T, Yref, H, scale=scale or None, self_term=self_term)
+    assert_blocks_close(host64(out), want, "bf16", f"B={B} C={C} S={S} d={d} q8={q8} self={self_term} scale={scale}")
