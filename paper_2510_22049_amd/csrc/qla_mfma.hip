@@ -252,6 +252,8 @@ __global__ __launch_bounds__(D * 2, 2) void qla_bwd_items_mfma_kernel(QlaParams 
   constexpr int CPT = kTile * CH / NT;
   constexpr bool kFence = D > 128;       // as in the forward kernel
   __shared__ uint4 xbuf[kRing][CH * 32];
+  constexpr int kStageRow = 80;                              // bytes between staged rows (64 used)
+  __shared__ uint4 stage[NW][2 * 32 * kStageRow / 16];       // per wave: dV^T rows, then dK^T rows
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -393,19 +395,33 @@ __global__ __launch_bounds__(D * 2, 2) void qla_bwd_items_mfma_kernel(QlaParams 
       gv = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zt[1], pk1.v, gv, 0, 0, 0);
       gp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zn[0], pv0.v, gp, 0, 0, 0);      // dP^T = dZs V^T
       gp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zn[1], pv1.v, gp, 0, 0, 0);
-      // lane = item l32 of the tile; register group of four = channels acc_row0(4 q) + 4 hf + 0..3
-      if (l32 < nvalid) {
-        const int64_t row = ca.row + l32;
+      // lane = item l32 of the tile; register group of four = channels acc_row0(4 q) + 4 hf + 0..3.
+      // The wave's two 32 x 32 result tiles pass through its own LDS patch (rows of 64 bytes,
+      // 80 apart) so that four lanes store one item's 64 contiguous bytes.
+      {
+        char* st = reinterpret_cast<char*>(stage[h]);
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-          const int64_t at = row * D + 32 * h + acc_row0(4 * q) + 4 * hf;
           uint2 ov, ok;
           ov.x = cvt_pk_bf16(gv[4 * q], gv[4 * q + 1]);
           ov.y = cvt_pk_bf16(gv[4 * q + 2], gv[4 * q + 3]);
           ok.x = cvt_pk_bf16(gp[4 * q] * dsilu[4 * q], gp[4 * q + 1] * dsilu[4 * q + 1]);
           ok.y = cvt_pk_bf16(gp[4 * q + 2] * dsilu[4 * q + 2], gp[4 * q + 3] * dsilu[4 * q + 3]);
-          *reinterpret_cast<uint2*>(dV + at) = ov;
-          *reinterpret_cast<uint2*>(dK + at) = ok;
+          const int at = l32 * kStageRow + (acc_row0(4 * q) + 4 * hf) * 2;
+          *reinterpret_cast<uint2*>(st + at) = ov;
+          *reinterpret_cast<uint2*>(st + 32 * kStageRow + at) = ok;
+        }
+        // (the wave reads back only what it wrote: program order within the wave is enough)
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+          const int r = 16 * half + (lane >> 2), c = lane & 3;
+          const uint4 ov = *reinterpret_cast<const uint4*>(st + r * kStageRow + 16 * c);
+          const uint4 ok = *reinterpret_cast<const uint4*>(st + (32 + r) * kStageRow + 16 * c);
+          if (r < nvalid) {
+            const int64_t at = (ca.row + r) * D + 32 * h + 8 * c;
+            *reinterpret_cast<uint4*>(dV + at) = ov;
+            *reinterpret_cast<uint4*>(dK + at) = ok;
+          }
         }
       }
       const int prev_user = ca.user;
