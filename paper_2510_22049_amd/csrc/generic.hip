@@ -407,7 +407,9 @@ __global__ __launch_bounds__(1024) void qla_bwd_state_kernel(const float* __rest
                                                             const int64_t* __restrict__ offsets, int S, int d, int H,
                                                             int seg, int64_t G, const T* __restrict__ Q,
                                                             int64_t q_user_stride, const T* __restrict__ dO,
-                                                            T* __restrict__ dQ, float* __restrict__ dz) {
+                                                            T* __restrict__ dQ, float* __restrict__ dz, int* status) {
+  // without a plan kernel in front (offsets checked on the host) the status word is cleared here
+  if (status && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *status = VISTA_OK;
   __shared__ float zs[kMaxDh * kMaxDh];        // Zs, then SiLU'(Zs)
   __shared__ float gt[kMaxDh * (kMaxDh + 1)];  // G transposed: gt[c][a]
   __shared__ float qa[64][kMaxDh + 1];         // SiLU(q) of the run
@@ -679,7 +681,7 @@ static vista_status qla_backward_t(const SummarizeArgs& a, const void* d_out, vo
   }
   VISTA_LAUNCH(qla_bwd_state_kernel<T>, dim3(d.B, d.H), dim3(1024), 0, a.stream, partials, a.offsets, d.S, d.d, d.H,
                a.seg, a.G, static_cast<const T*>(a.Q), d.q_user_stride, static_cast<const T*>(d_out),
-               static_cast<T*>(d_queries), dz);
+               static_cast<T*>(d_queries), dz, a.seg_user ? nullptr : reinterpret_cast<int*>(a.workspace));
   if (N > 0) {
     if (mfma) return mfma_qla_backward_items(a, dz, d_keys, d_values);
     const int64_t blocks = (N * d.H + 127) / 128;

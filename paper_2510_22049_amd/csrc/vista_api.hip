@@ -248,6 +248,12 @@ vista_status vista_qla_backward(const vista_summarize_desc* desc, const void* hi
   a.out_scales = nullptr;
   a.workspace = static_cast<char*>(workspace);
   a.stream = static_cast<hipStream_t>(hip_stream);
+  if (offsets_host && mfma_qla_supported(*desc)) {
+    // offsets already checked on the host: the streaming kernels find each segment's first user
+    // themselves and the state-gradient kernel clears the status word
+    a.seg_user = nullptr;
+    return qla_backward(a, d_out, d_queries, d_keys, d_values);
+  }
   int* seg_user = reinterpret_cast<int*>(a.workspace + kHeaderBytes);
   a.seg_user = seg_user;
   if (launch_plan(offsets, desc->B, desc->total_items, a.seg, a.G, reinterpret_cast<int*>(workspace), seg_user,
