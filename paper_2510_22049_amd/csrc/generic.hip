@@ -519,6 +519,156 @@ __global__ __launch_bounds__(1024) void qla_bwd_state_kernel(const float* __rest
   }
 }
 
+// The same for heads of width 32 (the matrix-core shapes), with the LDS traffic cut by register
+// blocking: a thread owns four neighbouring key channels, so one 16-byte and one 4-byte LDS
+// read feed four multiply-adds.  1024 threads; queries pass through LDS in runs of 256 (rows
+// 36 floats apart: 16-byte aligned, spread over the banks).
+//   dG:  thread (quarter g, key channels 4 ab .. 4 ab + 3, value channel c) sums over the
+//        run's rows 64 g .. 64 g + 63; the four quarters are added at the end as ((s0+s1)+s2)+s3;
+//   dQ:  thread (row, key channels 4 ab .. 4 ab + 3), two rows per thread and run.
+__device__ __forceinline__ void load4(const float* p, float v[4]) {
+  const float4 t = *reinterpret_cast<const float4*>(p);
+  v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+}
+__device__ __forceinline__ void load4(const bf16_t* p, float v[4]) {
+  const uint2 t = *reinterpret_cast<const uint2*>(p);
+  v[0] = __uint_as_float(t.x << 16); v[1] = __uint_as_float(t.x & 0xFFFF0000u);
+  v[2] = __uint_as_float(t.y << 16); v[3] = __uint_as_float(t.y & 0xFFFF0000u);
+}
+__device__ __forceinline__ void store4(float* p, const float v[4]) {
+  *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+}
+__device__ __forceinline__ void store4(bf16_t* p, const float v[4]) {
+  uint2 t;
+  t.x = uint32_t(f32_to_bf16_bits(v[0])) | (uint32_t(f32_to_bf16_bits(v[1])) << 16);
+  t.y = uint32_t(f32_to_bf16_bits(v[2])) | (uint32_t(f32_to_bf16_bits(v[3])) << 16);
+  *reinterpret_cast<uint2*>(p) = t;
+}
+
+template <typename T>
+__global__ __launch_bounds__(1024) void qla_bwd_state32_kernel(const float* __restrict__ partials,
+                                                               const int64_t* __restrict__ offsets, int S, int d, int H,
+                                                               int seg, int64_t G, const T* __restrict__ Q,
+                                                               int64_t q_user_stride, const T* __restrict__ dO,
+                                                               T* __restrict__ dQ, float* __restrict__ dz, int* status) {
+  constexpr int dh = 32, zz = dh * dh, kRun = 256, kRow = 36;
+  if (status && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *status = VISTA_OK;
+  __shared__ __align__(16) float zs[zz];                 // Zs, then SiLU'(Zs)
+  __shared__ __align__(16) float gt[dh * kRow];          // G transposed: gt[c][a]
+  __shared__ __align__(16) float qa[kRun * kRow];        // SiLU(q) of the run; at the end the partial dG of the four quarters
+  __shared__ __align__(16) float dy[kRun * kRow];        // dO of the run
+  const int b = blockIdx.x, h = blockIdx.y;
+  const int tid = threadIdx.x;
+  const int64_t begin = offsets[b], end = offsets[b + 1];
+  float* dzb = dz + (int64_t(b) * H + h) * zz;
+  T* dq = dQ + int64_t(b) * S * d + h * dh;
+  if (end <= begin) {       // no history: the forward output is zero whatever Q is
+    for (int e = tid; e < S * dh; e += 1024) store_as(dq + int64_t(e / dh) * d + (e % dh), 0.f);
+    dzb[tid] = 0.f;
+    return;
+  }
+  int64_t g0 = begin / seg, g1 = (end - 1) / seg;
+  if (g0 < 0) g0 = 0;
+  if (g1 > G - 1) g1 = G - 1;
+  const int grp = tid >> 8, t256 = tid & 255;
+  {   // the user's records in the finishing kernel's order
+    const int e = 4 * t256;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int64_t g = g0 + grp; g <= g1; g += 32) {
+      float4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        v[u] = g + 4 * u <= g1 ? *reinterpret_cast<const float4*>(partials + ((g + 4 * u + b) * H + h) * zz + e)
+                               : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        acc.x += v[u].x;
+        acc.y += v[u].y;
+        acc.z += v[u].z;
+        acc.w += v[u].w;
+      }
+    }
+    for (int turn = 0; turn < 4; ++turn) {
+      if (grp == turn) {
+        if (turn == 0) {
+          zs[e] = acc.x; zs[e + 1] = acc.y; zs[e + 2] = acc.z; zs[e + 3] = acc.w;
+        } else {
+          zs[e] += acc.x; zs[e + 1] += acc.y; zs[e + 2] += acc.z; zs[e + 3] += acc.w;
+        }
+      }
+      __syncthreads();
+    }
+  }
+  {
+    const float acc = zs[tid];             // entry (a, c) = (tid / 32, tid % 32)
+    zs[tid] = silu_prime_f(acc);
+    gt[(tid & 31) * kRow + (tid >> 5)] = silu_f(acc);
+  }
+  const int ab = t256 >> 5, c = t256 & 31;          // dG: key channels 4 ab .., value channel c
+  float dg[4] = {0.f, 0.f, 0.f, 0.f};
+  const T* Qb = Q + q_user_stride * b + h * dh;
+  const T* Db = dO + int64_t(b) * S * d + h * dh;
+  for (int i0 = 0; i0 < S; i0 += kRun) {
+    __syncthreads();
+    // eight elements of either array per thread, all loads issued before the first is used
+    {
+      float qv[8], yv[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int e = tid + 1024 * j, r = e >> 5, a = e & 31;
+        const bool on = i0 + r < S;
+        qv[j] = on ? to_f32(Qb[int64_t(i0 + r) * d + a]) : 0.f;
+        yv[j] = on ? to_f32(Db[int64_t(i0 + r) * d + a]) : 0.f;
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int e = tid + 1024 * j, r = e >> 5, a = e & 31;
+        qa[r * kRow + a] = silu_f(qv[j]);
+        dy[r * kRow + a] = yv[j];
+      }
+    }
+    __syncthreads();
+    // dG += SiLU(Q)^T dO over this quarter's 64 rows
+#pragma unroll 4
+    for (int r = 64 * grp; r < 64 * grp + 64; ++r) {
+      const float4 q4 = *reinterpret_cast<const float4*>(&qa[r * kRow + 4 * ab]);
+      const float y = dy[r * kRow + c];
+      dg[0] = fmaf(q4.x, y, dg[0]);
+      dg[1] = fmaf(q4.y, y, dg[1]);
+      dg[2] = fmaf(q4.z, y, dg[2]);
+      dg[3] = fmaf(q4.w, y, dg[3]);
+    }
+    // dQ = (dO G^T) * SiLU'(Q): rows tid / 8 and tid / 8 + 128, key channels 4 (tid % 8) ..
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int r = (tid >> 3) + 128 * j, a4 = 4 * (tid & 7);
+      if (i0 + r < S) {
+        float o[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 8
+        for (int cc = 0; cc < dh; ++cc) {
+          const float y = dy[r * kRow + cc];
+          const float4 g4 = *reinterpret_cast<const float4*>(&gt[cc * kRow + a4]);
+          o[0] = fmaf(y, g4.x, o[0]);
+          o[1] = fmaf(y, g4.y, o[1]);
+          o[2] = fmaf(y, g4.z, o[2]);
+          o[3] = fmaf(y, g4.w, o[3]);
+        }
+        float q[4];
+        load4(Qb + int64_t(i0 + r) * d + a4, q);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) o[k] *= silu_prime_f(q[k]);
+        store4(dq + int64_t(i0 + r) * d + a4, o);
+      }
+    }
+  }
+  // the four quarters' partial dG, added in a fixed order, times SiLU'(Zs)
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < 4; ++k) qa[grp * zz + (4 * ab + k) * dh + c] = dg[k];
+  __syncthreads();
+  dzb[tid] = (((qa[tid] + qa[zz + tid]) + qa[2 * zz + tid]) + qa[3 * zz + tid]) * zs[tid];
+}
+
 // Per item and head (plain path): dV = SiLU(k) dZs, dK = (v dZs^T) * SiLU'(k), from fp32 K, V.
 // One thread per (item, head).
 template <typename T>
@@ -679,9 +829,15 @@ static vista_status qla_backward_t(const SummarizeArgs& a, const void* d_out, vo
                    N, a.seg, a.seg_user, partials);
     }
   }
-  VISTA_LAUNCH(qla_bwd_state_kernel<T>, dim3(d.B, d.H), dim3(1024), 0, a.stream, partials, a.offsets, d.S, d.d, d.H,
-               a.seg, a.G, static_cast<const T*>(a.Q), d.q_user_stride, static_cast<const T*>(d_out),
-               static_cast<T*>(d_queries), dz, a.seg_user ? nullptr : reinterpret_cast<int*>(a.workspace));
+  int* status = a.seg_user ? nullptr : reinterpret_cast<int*>(a.workspace);
+  if (dh == 32)
+    VISTA_LAUNCH(qla_bwd_state32_kernel<T>, dim3(d.B, d.H), dim3(1024), 0, a.stream, partials, a.offsets, d.S, d.d, d.H,
+                 a.seg, a.G, static_cast<const T*>(a.Q), d.q_user_stride, static_cast<const T*>(d_out),
+                 static_cast<T*>(d_queries), dz, status);
+  else
+    VISTA_LAUNCH(qla_bwd_state_kernel<T>, dim3(d.B, d.H), dim3(1024), 0, a.stream, partials, a.offsets, d.S, d.d, d.H,
+                 a.seg, a.G, static_cast<const T*>(a.Q), d.q_user_stride, static_cast<const T*>(d_out),
+                 static_cast<T*>(d_queries), dz, status);
   if (N > 0) {
     if (mfma) return mfma_qla_backward_items(a, dz, d_keys, d_values);
     const int64_t blocks = (N * d.H + 127) / 128;
@@ -689,7 +845,6 @@ static vista_status qla_backward_t(const SummarizeArgs& a, const void* d_out, vo
     VISTA_LAUNCH(qla_bwd_items_kernel<T>, dim3(unsigned(blocks)), dim3(128), 0, a.stream, K, V, a.offsets, d.B, d.d,
                  d.H, N, dz, static_cast<T*>(d_keys), static_cast<T*>(d_values));
   }
-  (void)dh;
   return VISTA_OK;
 }
 

@@ -264,7 +264,8 @@ def qla_backward_oracle(X, off, Q, Wk, Wv, dO, H):
 
 @pytest.mark.parametrize("dtype,d,H,S,per_user", [("f32", 64, 2, 24, False), ("bf16", 64, 4, 40, True),
                                                   ("bf16", 128, 4, 256, False), ("bf16", 128, 4, 40, True),
-                                                  ("bf16", 256, 8, 128, False)])
+                                                  ("bf16", 256, 8, 128, False), ("bf16", 256, 8, 512, True),
+                                                  ("f32", 96, 3, 300, False), ("f32", 96, 2, 70, False)])
 @pytest.mark.parametrize("seg", [0, 96])
 def test_qla_backward(dtype, d, H, S, per_user, seg):
     """dQ per user, dK and dV per item against the oracle's gradients (App. B.1); jagged users incl.
