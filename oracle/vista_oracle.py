@@ -286,6 +286,34 @@ def qla_backward(Q, K, V, dO, H: int):
     return dQ, dK, dV
 
 
+def qla_backward_self(Q, K_self, V_self, dO, H: int):
+    """Gradients of the target-side diagonal term of quasi-linear attention (Sec. 3.2.2),
+        out_i += Delta(phi(Q), phi(K'))_ii v'_i = (phi(q_i) . phi(k'_i)) v'_i      per head,
+    with respect to Q, K' and V' (all [n, d]; K', V' are the targets' own keys and values),
+    given dO [n, d].  App. B.1 states them for the linear core (second term of Eq. 8, Eqs. 10
+    and 12) with the saved diagonals U = Delta(Q, K') and X = Delta(dO, V'):
+        dQ = X K',   dK' = X Q,   dV' = U dO.
+    With phi = SiLU in place the products are taken on the activated operands and each
+    gradient is multiplied by the derivative of its own activation:
+        U_i = phi(q_i) . phi(k'_i),   X_i = dO_i . v'_i
+        dQ_i = X_i phi(k'_i) * phi'(q_i),   dK'_i = X_i phi(q_i) * phi'(k'_i),   dV'_i = U_i dO_i.
+    Returns (dQ, dK', dV') in fp64; dQ is this term's share, to be added to that of
+    qla_backward."""
+    Q, Ks, Vs, dO = (np.asarray(a, dtype=F64) for a in (Q, K_self, V_self, dO))
+    d = Q.shape[1]
+    dh = d // H
+    dQ, dK, dV = np.zeros_like(Q), np.zeros_like(Ks), np.zeros_like(Vs)
+    for h in range(H):
+        c = slice(h * dh, (h + 1) * dh)
+        A, P = silu(Q[:, c]), silu(Ks[:, c])
+        U = (A * P).sum(axis=1)[:, None]
+        X = (dO[:, c] * Vs[:, c]).sum(axis=1)[:, None]
+        dQ[:, c] = X * P * silu_prime(Q[:, c])
+        dK[:, c] = X * A * silu_prime(Ks[:, c])
+        dV[:, c] = U * dO[:, c]
+    return dQ, dK, dV
+
+
 def quantize_summaries(Y, H: int):
     """Cache codec (Sec. 3.1 says the summaries are quantized for the cache and dequantized
     on use, and gives no scheme; this is the build's): symmetric int8 with one scale per

@@ -338,3 +338,55 @@ def test_qla_backward_with_identity_activation_is_eqs_7_9_11(monkeypatch):
     np.testing.assert_allclose(dQ, dO @ Z, rtol=1e-11)
     np.testing.assert_allclose(dK, V @ W.T, rtol=1e-11)
     np.testing.assert_allclose(dV, K @ W, rtol=1e-11)
+
+
+@pytest.mark.parametrize("H", [1, 2])
+def test_qla_backward_self_matches_autograd_and_finite_differences(H):
+    """The diagonal (self) term: autograd of a forward written with torch ops, and central
+    differences of the oracle's own forward (summarize_qla with the self term minus without,
+    which leaves exactly the diagonal term)."""
+    n, d = 4, 8
+    Q, Ks, Vs, dO = rnd(51, n, d), rnd(52, n, d), rnd(53, n, d), rnd(54, n, d)
+    dQ, dK, dV = O.qla_backward_self(Q, Ks, Vs, dO, H)
+    tq, tk, tv = (torch.tensor(a, requires_grad=True) for a in (Q, Ks, Vs))
+    dh = d // H
+    out = []
+    for h in range(H):
+        c = slice(h * dh, (h + 1) * dh)
+        u = (torch.nn.functional.silu(tq[:, c]) * torch.nn.functional.silu(tk[:, c])).sum(dim=1, keepdim=True)
+        out.append(u * tv[:, c])
+    (torch.cat(out, dim=1) * torch.from_numpy(dO)).sum().backward()
+    for got, want in ((dQ, tq.grad), (dK, tk.grad), (dV, tv.grad)):
+        np.testing.assert_allclose(got, want.numpy(), rtol=1e-10, atol=1e-12)
+
+    # the oracle's forward: K' = Q W_k and V' = Q W_v with W_k = W_v = I makes K' = V' = Q, so
+    # perturbing one seed entry moves all three; the chain rule sums the three gradients
+    X = rnd(55, 5, d)
+    I8 = np.eye(d)
+    def diag_term(Qx):
+        return (O.summarize_qla(X, [0, 5], Qx, I8, I8, H, self_term=True)
+                - O.summarize_qla(X, [0, 5], Qx, I8, I8, H))[0]
+    gQ, gK, gV = O.qla_backward_self(Q, Q, Q, dO, H)
+    total = gQ + gK + gV
+    eps = 1e-6
+    for idx in ((0, 0), (2, 5), (3, 7)):
+        hi, lo = Q.copy(), Q.copy()
+        hi[idx] += eps; lo[idx] -= eps
+        fd = ((diag_term(hi) - diag_term(lo)) * dO).sum() / (2 * eps)
+        assert abs(fd - total[idx]) <= 1e-6 * max(1.0, abs(fd))
+
+
+def test_qla_backward_self_with_identity_activation_is_eqs_8_10_12(monkeypatch):
+    """App. B.1, target part of the linear core: with U = Delta(Q, K') and X = Delta(dO, V') kept as
+    diagonals, dQ gains X K', dK' = X Q and dV' = U dO."""
+    monkeypatch.setattr(O, "silu", lambda x: x)
+    monkeypatch.setattr(O, "silu_prime", lambda x: np.ones_like(x))
+    Q, Ks, Vs, dO = rnd(56, 4, 8), rnd(57, 4, 8), rnd(58, 4, 8), rnd(59, 4, 8)
+    dQ, dK, dV = O.qla_backward_self(Q, Ks, Vs, dO, 1)
+    U = np.diag((Q * Ks).sum(axis=1))
+    Xd = np.diag((dO * Vs).sum(axis=1))
+    np.testing.assert_allclose(dQ, Xd @ Ks, rtol=1e-12)
+    np.testing.assert_allclose(dK, Xd @ Q, rtol=1e-12)
+    np.testing.assert_allclose(dV, U @ dO, rtol=1e-12)
+    # a planted mistake (the two diagonals swapped) is caught
+    assert np.abs(U @ Ks - dQ).max() > 1e-3
