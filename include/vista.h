@@ -250,11 +250,22 @@ vista_status vista_target_attend(const vista_attend_desc* desc,
  * gradients are with respect to these projected keys and values (their own backward --
  * dX = dK W_k^T + dV W_v^T, dW = X^T dK -- is a pair of plain matrix products outside this path).
  *
- *   desc            as for the forward call: attn = VISTA_ATTN_QLA, flags = 0, scale = 0
+ * With VISTA_FLAG_SELF_TERM the forward output also holds the target-side diagonal term
+ * (SiLU(q_i) . SiLU(k'_i)) v'_i with the seeds' own k' = q W_k, v' = q W_v (Sec. 3.2.2); its
+ * gradients (App. B.1: the second term of Eq. 8, Eqs. 10 and 12, with the diagonals
+ * U = Delta(SiLU(Q), SiLU(K')) and X = Delta(dO, V')) are
+ *     dV' = U dO,   dK' = X SiLU(Q) * SiLU'(K'),   dQ += X SiLU(K') * SiLU'(Q)
+ * with respect to k' and v' as values of their own (the chain through q W_k, q W_v is the
+ * caller's, as for the history).
+ *
+ *   desc            as for the forward call: attn = VISTA_ATTN_QLA, scale = 0, flags = 0 or
+ *                   VISTA_FLAG_SELF_TERM
  *   d_out           device [B, S, d]  dtype   gradient of the loss w.r.t. the forward output
  *   d_queries       device [B, S, d]  dtype   per user, also when the queries are shared
  *                                             (the gradient of shared seeds is the sum over users)
  *   d_keys, d_values device [N, d]    dtype   rows of users without history do not exist; every row is written
+ *   d_self_keys, d_self_values  device [B, S, d]  dtype   with VISTA_FLAG_SELF_TERM only (else
+ *                   ignored, may be NULL): per user, zeros for users without history
  *   workspace       >= vista_qla_backward_workspace_bytes(desc), 256-byte aligned
  * Supported: the shapes vista_summarize takes with VISTA_ATTN_QLA.
  */
@@ -270,6 +281,8 @@ vista_status vista_qla_backward(const vista_summarize_desc* desc,
                                 void* d_queries,
                                 void* d_keys,
                                 void* d_values,
+                                void* d_self_keys,
+                                void* d_self_values,
                                 void* workspace, size_t workspace_bytes,
                                 void* hip_stream);
 

@@ -100,7 +100,7 @@ def lib() -> C.CDLL:
     L.vista_qla_backward_workspace_bytes.restype = C.c_size_t
     L.vista_qla_backward_workspace_bytes.argtypes = [C.POINTER(SummarizeDesc)]
     L.vista_qla_backward.restype = C.c_int
-    L.vista_qla_backward.argtypes = [C.POINTER(SummarizeDesc)] + [vp] * 11 + [C.c_size_t, vp]
+    L.vista_qla_backward.argtypes = [C.POINTER(SummarizeDesc)] + [vp] * 13 + [C.c_size_t, vp]
     L.vista_quantize_summaries.restype = C.c_int
     L.vista_quantize_summaries.argtypes = [C.POINTER(CodecDesc), vp, vp, vp, vp]
     L.vista_target_attend_q8.restype = C.c_int
@@ -220,13 +220,16 @@ def vista_summarize_q8(history_emb, offsets, virtual_queries, W_k, W_v, out_code
 
 
 def vista_qla_backward(history_emb, offsets, virtual_queries, W_k, W_v, d_out, d_queries, d_keys, d_values, *, H,
-                       segment_items=0, offsets_host=None, workspace=None):
-    """Gradients of quasi-linear attention: d_out [B,S,d] -> d_queries [B,S,d], d_keys / d_values [N,d]."""
+                       segment_items=0, offsets_host=None, workspace=None, d_self_keys=None, d_self_values=None):
+    """Gradients of quasi-linear attention: d_out [B,S,d] -> d_queries [B,S,d], d_keys / d_values [N,d];
+    with d_self_keys / d_self_values [B,S,d] given, the forward had the self term and its gradients
+    are formed as well."""
     B = offsets.numel() - 1
     S, d = virtual_queries.shape[-2:]
     N = history_emb.shape[0]
+    self_term = d_self_keys is not None or d_self_values is not None
     desc = summarize_desc(B, S, d, H, _dtype_code(history_emb), N, virtual_queries.dim() == 3, 0.0,
-                          segment_items, VISTA_ATTN_QLA)
+                          segment_items, VISTA_ATTN_QLA, self_term)
     need = lib().vista_qla_backward_workspace_bytes(C.byref(desc))
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=history_emb.device)
@@ -235,8 +238,10 @@ def vista_qla_backward(history_emb, offsets, virtual_queries, W_k, W_v, d_out, d
                                   _dev(offsets, "offsets"), host, _dev(virtual_queries, "virtual_queries"),
                                   _dev(W_k, "W_k"), _dev(W_v, "W_v"), _dev(d_out, "d_out"),
                                   _dev(d_queries, "d_queries"), _dev(d_keys, "d_keys") if N else None,
-                                  _dev(d_values, "d_values") if N else None, _dev(workspace, "workspace"),
-                                  workspace.numel(), _stream())
+                                  _dev(d_values, "d_values") if N else None,
+                                  _dev(d_self_keys, "d_self_keys") if d_self_keys is not None else None,
+                                  _dev(d_self_values, "d_self_values") if d_self_values is not None else None,
+                                  _dev(workspace, "workspace"), workspace.numel(), _stream())
     if st != VISTA_OK:
         raise VistaError(st)
     return workspace

@@ -191,7 +191,8 @@ vista_status mfma_qla_state(const SummarizeArgs& a, float* partials);
 // dz: dZs [B][H][32][32] fp32 (device); writes dK and dV rows of every item
 vista_status mfma_qla_backward_items(const SummarizeArgs& a, const float* dz, void* d_keys, void* d_values);
 size_t qla_backward_workspace(const vista_summarize_desc& d, int seg);
-vista_status qla_backward(const SummarizeArgs& a, const void* d_out, void* d_queries, void* d_keys, void* d_values);
+vista_status qla_backward(const SummarizeArgs& a, const void* d_out, void* d_queries, void* d_keys, void* d_values,
+                          void* d_self_keys, void* d_self_values);
 
 // summaries either as `summ` (dtype) or, when codes != null, as int8 codes with fp32 scales [B, S, H]
 vista_status generic_target_attend(const vista_attend_desc& d, float scale_log2, const void* cand,

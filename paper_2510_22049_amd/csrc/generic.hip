@@ -669,6 +669,52 @@ __global__ __launch_bounds__(1024) void qla_bwd_state32_kernel(const float* __re
   dzb[tid] = (((qa[tid] + qa[zz + tid]) + qa[2 * zz + tid]) + qa[3 * zz + tid]) * zs[tid];
 }
 
+// Gradients of the target-side diagonal term (phi(q_i) . phi(k'_i)) v'_i (App. B.1: second term of
+// Eq. 8, Eqs. 10 and 12, with phi = SiLU in place), one wave-sized group of dh threads per
+// (user, query, head):
+//   U = phi(q) . phi(k'),  X = dO . v',
+//   dV' = U dO,   dK' = X phi(q) * phi'(k'),   dQ += X phi(k') * phi'(q)   (added to what the
+//   state-gradient kernel has written).  Users without history get zeros (their output is zero).
+template <typename T>
+__global__ void qla_bwd_self_kernel(const T* __restrict__ Q, int64_t q_user_stride, const float* __restrict__ Ks,
+                                    const float* __restrict__ Vs, const T* __restrict__ dO,
+                                    const int64_t* __restrict__ offsets, int B, int S, int d, int H,
+                                    T* __restrict__ dQ, T* __restrict__ dKs, T* __restrict__ dVs) {
+  const int dh = d / H;
+  const int64_t unit = int64_t(blockIdx.x) * blockDim.y + threadIdx.y;      // (user, query, head)
+  if (unit >= int64_t(B) * S * H) return;
+  const int h = int(unit % H);
+  const int64_t bi = unit / H;                                            // user * S + query
+  const int b = int(bi / S), i = int(bi % S);
+  const int t = threadIdx.x;                                              // channel of the head (blockDim.x = 64)
+  const int64_t at = bi * d + h * dh + t;
+  const bool on = t < dh;
+  if (offsets[b + 1] <= offsets[b]) {
+    if (on) {
+      store_as(dKs + at, 0.f);
+      store_as(dVs + at, 0.f);
+    }
+    return;
+  }
+  const int64_t srow = (q_user_stride ? int64_t(b) * S : 0) + i;
+  const float q = on ? to_f32(Q[q_user_stride * b + int64_t(i) * d + h * dh + t]) : 0.f;
+  const float k = on ? Ks[srow * d + h * dh + t] : 0.f;
+  const float v = on ? Vs[srow * d + h * dh + t] : 0.f;
+  const float g = on ? to_f32(dO[at]) : 0.f;
+  const float a = silu_f(q), pk = silu_f(k);
+  float u = a * pk, x = g * v;
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    u += __shfl_xor(u, off, 64);
+    x += __shfl_xor(x, off, 64);
+  }
+  if (on) {
+    store_as(dVs + at, u * g);
+    store_as(dKs + at, x * a * silu_prime_f(k));
+    store_as(dQ + at, to_f32(dQ[at]) + x * pk * silu_prime_f(q));
+  }
+}
+
 // Per item and head (plain path): dV = SiLU(k) dZs, dK = (v dZs^T) * SiLU'(k), from fp32 K, V.
 // One thread per (item, head).
 template <typename T>
@@ -805,7 +851,7 @@ size_t qla_backward_workspace(const vista_summarize_desc& d, int seg) {
 
 template <typename T>
 static vista_status qla_backward_t(const SummarizeArgs& a, const void* d_out, void* d_queries, void* d_keys,
-                                   void* d_values) {
+                                   void* d_values, void* d_self_keys, void* d_self_values) {
   const vista_summarize_desc& d = a.desc;
   const int64_t N = d.total_items;
   const int dh = d.d / d.H;
@@ -838,6 +884,18 @@ static vista_status qla_backward_t(const SummarizeArgs& a, const void* d_out, vo
     VISTA_LAUNCH(qla_bwd_state_kernel<T>, dim3(d.B, d.H), dim3(1024), 0, a.stream, partials, a.offsets, d.S, d.d, d.H,
                  a.seg, a.G, static_cast<const T*>(a.Q), d.q_user_stride, static_cast<const T*>(d_out),
                  static_cast<T*>(d_queries), dz, status);
+  if (d.flags & VISTA_FLAG_SELF_TERM) {
+    // the seeds' own keys and values, then the diagonal term's gradients (dQ is added to)
+    float* Ks = V + kv_each / sizeof(float);
+    float* Vs = Ks + self_kv_bytes(d) / sizeof(float);
+    if (launch_self_kv(d, a.Q, a.Wk, a.Wv, Ks, Vs, a.stream) != hipSuccess) return VISTA_ERR_HIP;
+    const int64_t units = int64_t(d.B) * d.S * d.H;
+    const int64_t blocks = (units + 3) / 4;
+    if (blocks > 0x7FFFFFFF) return VISTA_ERR_UNSUPPORTED;
+    VISTA_LAUNCH(qla_bwd_self_kernel<T>, dim3(unsigned(blocks)), dim3(64, 4), 0, a.stream, static_cast<const T*>(a.Q),
+                 d.q_user_stride, Ks, Vs, static_cast<const T*>(d_out), a.offsets, d.B, d.S, d.d, d.H,
+                 static_cast<T*>(d_queries), static_cast<T*>(d_self_keys), static_cast<T*>(d_self_values));
+  }
   if (N > 0) {
     if (mfma) return mfma_qla_backward_items(a, dz, d_keys, d_values);
     const int64_t blocks = (N * d.H + 127) / 128;
@@ -848,9 +906,11 @@ static vista_status qla_backward_t(const SummarizeArgs& a, const void* d_out, vo
   return VISTA_OK;
 }
 
-vista_status qla_backward(const SummarizeArgs& a, const void* d_out, void* d_queries, void* d_keys, void* d_values) {
-  return a.desc.dtype == VISTA_BF16 ? qla_backward_t<bf16_t>(a, d_out, d_queries, d_keys, d_values)
-                                    : qla_backward_t<float>(a, d_out, d_queries, d_keys, d_values);
+vista_status qla_backward(const SummarizeArgs& a, const void* d_out, void* d_queries, void* d_keys, void* d_values,
+                          void* d_self_keys, void* d_self_values) {
+  return a.desc.dtype == VISTA_BF16
+             ? qla_backward_t<bf16_t>(a, d_out, d_queries, d_keys, d_values, d_self_keys, d_self_values)
+             : qla_backward_t<float>(a, d_out, d_queries, d_keys, d_values, d_self_keys, d_self_values);
 }
 
 // ------------------------------------------------------------------ stage 2

@@ -211,18 +211,20 @@ vista_status vista_quantize_summaries(const vista_codec_desc* desc, const void* 
 }
 
 size_t vista_qla_backward_workspace_bytes(const vista_summarize_desc* desc) {
-  if (check_summarize_desc(desc) != VISTA_OK || desc->attn != VISTA_ATTN_QLA || desc->flags != 0) return 0;
+  if (check_summarize_desc(desc) != VISTA_OK || desc->attn != VISTA_ATTN_QLA) return 0;
   return qla_backward_workspace(*desc, resolve_segment(desc));
 }
 
 vista_status vista_qla_backward(const vista_summarize_desc* desc, const void* history_emb, const int64_t* offsets,
                                 const int64_t* offsets_host, const void* virtual_queries, const void* W_k,
                                 const void* W_v, const void* d_out, void* d_queries, void* d_keys, void* d_values,
-                                void* workspace, size_t workspace_bytes, void* hip_stream) {
+                                void* d_self_keys, void* d_self_values, void* workspace, size_t workspace_bytes,
+                                void* hip_stream) {
   vista_status st = check_summarize_desc(desc);
   if (st != VISTA_OK) return st;
-  if (desc->attn != VISTA_ATTN_QLA || desc->flags != 0) return VISTA_ERR_UNSUPPORTED;
+  if (desc->attn != VISTA_ATTN_QLA) return VISTA_ERR_UNSUPPORTED;
   if (!offsets || !virtual_queries || !W_k || !W_v || !d_out || !d_queries) return VISTA_ERR_NULL;
+  if ((desc->flags & VISTA_FLAG_SELF_TERM) && (!d_self_keys || !d_self_values)) return VISTA_ERR_NULL;
   if (desc->total_items > 0 && (!history_emb || !d_keys || !d_values)) return VISTA_ERR_NULL;
   if (offsets_host) {
     if (offsets_host[0] != 0 || offsets_host[desc->B] != desc->total_items) return VISTA_ERR_OFFSETS;
@@ -252,14 +254,14 @@ vista_status vista_qla_backward(const vista_summarize_desc* desc, const void* hi
     // offsets already checked on the host: the streaming kernels find each segment's first user
     // themselves and the state-gradient kernel clears the status word
     a.seg_user = nullptr;
-    return qla_backward(a, d_out, d_queries, d_keys, d_values);
+    return qla_backward(a, d_out, d_queries, d_keys, d_values, d_self_keys, d_self_values);
   }
   int* seg_user = reinterpret_cast<int*>(a.workspace + kHeaderBytes);
   a.seg_user = seg_user;
   if (launch_plan(offsets, desc->B, desc->total_items, a.seg, a.G, reinterpret_cast<int*>(workspace), seg_user,
                   a.stream) != hipSuccess)
     return VISTA_ERR_HIP;
-  return qla_backward(a, d_out, d_queries, d_keys, d_values);
+  return qla_backward(a, d_out, d_queries, d_keys, d_values, d_self_keys, d_self_values);
 }
 
 vista_status vista_summarize_static(const vista_summarize_desc* desc, const void* history_emb,

@@ -150,7 +150,8 @@ def test_qla_backward_rejects_bad_arguments():
     L = V.lib()
     one = C.c_void_p(256)
     args = lambda d, **kw: [C.byref(d)] + [kw.get(k, one) for k in
-                                            ("x", "off", "off_host", "q", "wk", "wv", "do", "dq", "dk", "dv", "ws")] + \
+                                            ("x", "off", "off_host", "q", "wk", "wv", "do", "dq", "dk", "dv", "dks", "dvs",
+                                             "ws")] + \
         [kw.get("bytes", 1 << 30), None]
     d = desc()                                                          # softmax form: no gradients here
     assert L.vista_qla_backward(*args(d, off_host=None)) == V.VISTA_ERR_UNSUPPORTED
@@ -164,8 +165,10 @@ def test_qla_backward_rejects_bad_arguments():
     need = L.vista_qla_backward_workspace_bytes(C.byref(d))
     assert need > V.vista_summarize_workspace_bytes(d) > 0
     assert L.vista_qla_backward(*args(d, off_host=good.ctypes.data, bytes=need - 1)) == V.VISTA_ERR_WORKSPACE
-    d.flags = V.VISTA_FLAG_SELF_TERM                                    # gradients of the self term are not built
-    assert L.vista_qla_backward(*args(d, off_host=good.ctypes.data)) == V.VISTA_ERR_UNSUPPORTED
+    d.flags = V.VISTA_FLAG_SELF_TERM                                    # the self term needs its two outputs
+    assert L.vista_qla_backward_workspace_bytes(C.byref(d)) > need
+    assert L.vista_qla_backward(*args(d, off_host=good.ctypes.data, dks=None)) == V.VISTA_ERR_NULL
+    assert L.vista_qla_backward(*args(d, off_host=good.ctypes.data, dvs=None)) == V.VISTA_ERR_NULL
 
 
 def test_static_entry_point_rejects_what_does_not_fit_its_array():

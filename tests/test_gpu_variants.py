@@ -395,3 +395,41 @@ def test_random_stage2_shapes(seed):
     torch.cuda.synchronize()
     want = O.target_attend(T, Yref, H, scale=scale or None, self_term=self_term)
     assert_blocks_close(host64(out), want, "bf16", f"B={B} C={C} S={S} d={d} q8={q8} self={self_term} scale={scale}")
+
+
+@pytest.mark.parametrize("dtype,d,H,S,per_user", [("f32", 64, 2, 24, False), ("bf16", 128, 4, 256, False),
+                                                  ("bf16", 256, 8, 128, True), ("f32", 96, 2, 70, True)])
+def test_qla_backward_with_the_self_term(dtype, d, H, S, per_user):
+    """The diagonal term's gradients (App. B.1: second term of Eq. 8, Eqs. 10 and 12): dK', dV' per
+    user and seed, and dQ as the sum of both parts; users without history get zeros."""
+    lens = [700, 0, 33, 1100, 1]
+    X, off, Q, Wk, Wv = problem(71, lens, d, S, dtype, per_user)
+    g = np.random.default_rng(72)
+    B = len(lens)
+    dO = I.round_to(g.normal(size=(B, S, d)).astype(np.float32), dtype)
+    tdt = torch_dtype(dtype)
+    new = lambda shape: torch.full(shape, float("nan"), device="cuda", dtype=tdt)
+    dQ, dK, dV, dKs, dVs = new((B, S, d)), new(X.shape), new(X.shape), new((B, S, d)), new((B, S, d))
+    ws = V.vista_qla_backward(dev(X, dtype), torch.from_numpy(off).cuda(), dev(Q, dtype), dev(Wk, dtype), dev(Wv, dtype),
+                              dev(dO, dtype), dQ, dK, dV, H=H, offsets_host=torch.from_numpy(off),
+                              d_self_keys=dKs, d_self_values=dVs)
+    torch.cuda.synchronize()
+    assert int(ws[:4].view(torch.int32).item()) == 0
+    wQ, wK, wV = qla_backward_oracle(X, off, Q, Wk, Wv, dO, H)
+    wKs, wVs = np.zeros((B, S, d)), np.zeros((B, S, d))
+    for b in range(B):
+        if off[b + 1] > off[b]:
+            q = (Q[b] if per_user else Q).astype(np.float64)
+            sq, wKs[b], wVs[b] = O.qla_backward_self(q, q @ Wk.astype(np.float64), q @ Wv.astype(np.float64), dO[b], H)
+            wQ[b] += sq
+    assert_blocks_close(host64(dQ), wQ, dtype, "dQ with the self term")
+    assert_blocks_close(host64(dKs), wKs, dtype, "dK'")
+    assert_blocks_close(host64(dVs), wVs, dtype, "dV'")
+    assert np.all(host64(dKs)[1] == 0) and np.all(host64(dVs)[1] == 0) and np.all(host64(dQ)[1] == 0)
+    # the history's gradients are those of the call without the self term
+    tol = 5e-2 if dtype == "bf16" else TOL[dtype]
+    for b in range(B):
+        if off[b + 1] > off[b]:
+            sl = slice(off[b], off[b + 1])
+            for got_, want_ in ((host64(dK)[sl], wK[sl]), (host64(dV)[sl], wV[sl])):
+                assert block_errors(got_[None], want_[None])[0] <= tol
