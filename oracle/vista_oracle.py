@@ -32,8 +32,9 @@ What is computed (every function below cites the passage it follows):
   "quantized ... and dequantized" (Sec. 3.1); the paper gives no scheme, this
   build's is stated in the functions.
 * ``qla_backward``: gradients of the quasi-linear form with respect to Q, K, V
-  (App. B.1, Eqs. 7-12 for the linear core; the activation factors follow the
-  pattern the appendix shows for its shifted-ELU variant).
+  (App. B.1, Eqs. 7, 9, 11 for the linear core; the activation factors follow the
+  pattern the appendix shows for its shifted-ELU variant); ``qla_backward_self``:
+  those of the target-side diagonal term (second term of Eq. 8, Eqs. 10 and 12).
 
 Every result has a plain closed definition, so the code is that definition:
 two-pass softmax, no tiling, no running maximum, no fusion.  numpy's matmul
